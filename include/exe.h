@@ -1,0 +1,220 @@
+/*
+ * exe -- batched Transformer execution on one MI355X (gfx950): the per-GPU model execution that an
+ * execution-schedule-driven LLM inference engine runs and that its profiler times.
+ *
+ * The computation is the one the paper's background section describes (Section 2): a batch of
+ * variable-length inputs is ENCODED once; then DECODE iterations each produce one token per live
+ * sequence, reading that sequence's memoized keys/values (incremental decoding).  Attention runs per
+ * sequence, everything else runs on the packed batch (selective batching, Section 2, review of ORCA).
+ * Sequences that are finished leave the batch (early termination, Section 3 "XRunner") and sequences
+ * from different encode calls may share a decode batch (decoupled batches, Section 6).  exe_profile
+ * emits the per-layer attention / rest-of-layer latency table (Section 3 "XProfiler").
+ *
+ * Conventions
+ *  - Every call returns an int: EXE_OK (0) or a negative exe_status.  Nothing throws or aborts on bad
+ *    input; exe_last_error() returns a thread-local description of the last failure.
+ *  - "host" pointers are ordinary CPU memory read/written before the call returns.  "device" pointers
+ *    are HIP device memory on the current device, owned by the caller.
+ *  - Calls are synchronous: when they return, host outputs are filled and device outputs are complete
+ *    on the model's stream (the stream has been synchronised).
+ *  - A model handle is not thread-safe; use one handle per thread.
+ *  - Linear weights are [out_features, in_features] row-major in the model's dtype.  The fused QKV
+ *    weight's rows are [all query heads | all key heads | all value heads], head-major.
+ */
+#ifndef EXE_H
+#define EXE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct exe_model exe_model_t;
+
+enum exe_status {
+    EXE_OK = 0,
+    EXE_ERR_ARG = -1,           /* NULL pointer, negative count, bad enum value */
+    EXE_ERR_SHAPE = -2,         /* config/shape not supported by the kernels */
+    EXE_ERR_OOM_KV = -3,        /* key/value pool or a sequence's reserved capacity exhausted */
+    EXE_ERR_BAD_SEQ = -4,       /* unknown, duplicate, already-live or released sequence id */
+    EXE_ERR_BAD_LENGTH = -5,    /* a length argument contradicts the library's own bookkeeping */
+    EXE_ERR_HIP = -6,           /* a HIP call failed (message carries the HIP error string) */
+    EXE_ERR_UNIMPLEMENTED = -7
+};
+
+enum { EXE_ARCH_DECODER_ONLY = 0, EXE_ARCH_ENC_DEC = 1 };
+enum { EXE_ACT_RELU = 0, EXE_ACT_GELU = 1 };          /* GELU is the erf form */
+enum { EXE_NORM_LAYERNORM = 0, EXE_NORM_RMSNORM = 1 };
+enum { EXE_POS_LEARNED = 0, EXE_POS_RELBIAS = 1, EXE_POS_NONE = 2 };
+enum { EXE_DTYPE_F32 = 0, EXE_DTYPE_BF16 = 1 };
+enum { EXE_SCALE_RSQRT_DH = 0, EXE_SCALE_NONE = 1 };
+
+typedef struct exe_config {
+    int32_t arch;            /* EXE_ARCH_* */
+    int32_t n_layers;        /* decoder-only: layers; enc-dec: encoder layers */
+    int32_t n_dec_layers;    /* enc-dec: decoder layers; 0 otherwise */
+    int32_t d_model, n_heads, head_dim, d_ff, vocab;
+    int32_t max_pos;         /* rows of the learned position table (EXE_POS_LEARNED) */
+    int32_t act, norm, pos;
+    int32_t rel_buckets, rel_max_dist;   /* EXE_POS_RELBIAS: T5 bucket scheme parameters */
+    int32_t cross_rel_bias;  /* enc-dec: 1 = cross-attention adds a bidirectional relative-position bias */
+    int32_t dtype;           /* storage type of weights, activations between kernels and the K/V cache */
+    int32_t has_embed;       /* 0: callers pass hidden states [tokens, d_model] instead of token ids */
+    int32_t has_lm_head;     /* 0: calls return hidden states instead of logits/tokens */
+    int32_t scale_mode;      /* EXE_SCALE_* for attention scores */
+    float norm_eps;
+    uint64_t kv_pool_bytes;  /* size of the key/value pool the model allocates */
+    int32_t max_seqs;        /* sequence ids are 0 .. max_seqs-1 */
+    int32_t max_batch_tokens;/* largest sum of input lengths in one exe_encode (workspace size) */
+    int32_t max_batch_seqs;  /* largest number of sequences in one exe_encode / exe_decode_step call */
+} exe_config_t;
+
+/* A weight tensor: device pointer, dtype = config.dtype. */
+typedef struct exe_tensor { const void* ptr; } exe_tensor_t;
+
+/*
+ * Weight order (paper Section 2 names the pieces; the layout is this library's):
+ *  decoder-only: [tok_emb [V,d]] (if has_embed or has_lm_head), [pos_emb [max_pos,d]] (if has_embed and
+ *    learned positions), then per layer: ln1_g, ln1_b, w_qkv [3*H*dh, d], b_qkv, w_o [d, H*dh], b_o,
+ *    ln2_g, ln2_b, w_1 [d_ff, d], b_1, w_2 [d, d_ff], b_2; then lnf_g, lnf_b (if has_lm_head).
+ *    The LM head is tied to tok_emb, no bias.
+ *  enc-dec: tok_emb, enc_rel_bias [buckets, H], dec_rel_bias [buckets, H], [cross_rel_bias [buckets, H]],
+ *    per encoder layer: rms1_g, w_qkv, w_o, rms2_g, w_1, w_2; enc_final_g;
+ *    per decoder layer: rms1_g, w_qkv, w_o, rmsx_g, w_xq [H*dh, d], w_xkv [2*H*dh, d], w_xo, rms3_g, w_1, w_2;
+ *    dec_final_g.  No biases; logits = (final-normed hidden * d^-1/2) . tok_emb^T.
+ */
+int exe_expected_weights(const exe_config_t* cfg);   /* number of tensors, or a negative status */
+
+/* Creates a model.  `weights` (host array of n_weights entries) are device tensors BORROWED until
+ * exe_model_free.  `hip_stream` is a hipStream_t (NULL = the default stream) on which all work is
+ * enqueued.  Allocates the K/V pool (cfg->kv_pool_bytes) and the activation workspace. */
+int exe_model_load(const exe_config_t* cfg, const exe_tensor_t* weights, int32_t n_weights,
+                   void* hip_stream, exe_model_t** out);
+int exe_model_free(exe_model_t* m);
+
+/*
+ * Encode (prefill) n sequences (Section 2: "encoding the input once").
+ *  seq_ids [n] host: caller-chosen, unique, not live, in [0, max_seqs).
+ *  input_lengths [n] host (>= 1); tokens_packed [sum lengths] host, sequence after sequence
+ *    (ignored if !has_embed; then hidden_in [sum lengths, d_model] device is read instead).
+ *  reserve_lengths [n] host, nullable: K/V capacity of each sequence in positions (decoder-only: input +
+ *    all outputs; enc-dec: decoder positions).  NULL reserves input+256 (decoder-only, capped at max_pos
+ *    for learned positions) or 256 (enc-dec).
+ *  next_tokens [n] host, nullable: decoder-only with LM head: greedy first generated token (lowest index
+ *    on ties).  enc-dec: not written (the encoder generates nothing).
+ *  out_device nullable device: decoder-only with LM head: float logits [n, vocab] of the last position;
+ *    decoder-only without LM head: hidden states [sum lengths, d_model] in dtype; enc-dec: encoder output
+ *    [sum lengths, d_model] in dtype.
+ * On any error nothing is admitted (no sequence becomes live).
+ */
+int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, const int32_t* input_lengths,
+               const int32_t* tokens_packed, const int32_t* reserve_lengths, const void* hidden_in,
+               int32_t* next_tokens, void* out_device);
+
+/*
+ * One decode iteration for n live sequences (Section 2: "each decoding iteration producing a single
+ * output token"; the batch may mix sequences from different encode calls and shrinks as sequences finish).
+ *  tokens_in [n] host: the token fed at this step (decoder-only: the previously generated token;
+ *    enc-dec: the start token, then the previously generated token).  Ignored if !has_embed: then
+ *    hidden_in [n, d_model] device.
+ *  kv_lengths [n] host: self-attention K/V length AFTER this token is appended; must equal the library's
+ *    own count + 1, else EXE_ERR_BAD_LENGTH and no state changes.
+ *  next_tokens [n] host nullable; out_device nullable: float logits [n, vocab] or hidden [n, d_model].
+ */
+int exe_decode_step(exe_model_t* m, int32_t n, const int32_t* seq_ids, const int32_t* tokens_in,
+                    const int32_t* kv_lengths, const void* hidden_in, int32_t* next_tokens, void* out_device);
+
+/* Early termination: the sequences leave; their K/V extents return to the pool. */
+int exe_seq_release(exe_model_t* m, int32_t n, const int32_t* seq_ids);
+
+/* Current K/V length of a live sequence (decoder-only: positions memoized; enc-dec: decoder positions),
+ * or a negative status. */
+int exe_seq_length(exe_model_t* m, int32_t seq_id);
+
+/* Pool accounting (bytes). Any pointer may be NULL. */
+int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used_bytes, uint64_t* largest_free_bytes,
+                 int32_t* live_seqs);
+
+/*
+ * Latency table for a scheduler (Section 3 "XProfiler": for a single layer, the attention kernel is
+ * timed separately from the rest of the layer, over batch sizes and sequence lengths).
+ *  phase 0: encode -- `batch` sequences of `length` input tokens (or lengths drawn from `dist`).
+ *  phase 1: decode -- `batch` sequences whose K/V length is `length` (or drawn from `dist`).
+ * One row per (batch, length) pair, batch-major.  Times are per layer, in milliseconds, averaged over
+ * n_steps timed repetitions after 3 warm-up ones; K/V of a single layer is allocated from the model's pool,
+ * which must hold no live sequence.  full_step_ms = n_layers*(attn+rest) + head_ms is an extrapolation.
+ */
+typedef struct exe_profile_row {
+    int32_t phase, batch, length, ragged;
+    int32_t total_tokens;          /* encode: sum of lengths; decode: sum of K/V lengths */
+    float attn_ms_per_layer, rest_ms_per_layer, head_ms, full_step_ms, std_ms;
+    int32_t n_timed;
+} exe_profile_row_t;
+typedef struct exe_length_dist {
+    int32_t kind;                  /* 0 fixed (= the row's length), 1 normal, rounded, clipped to [lo, hi] */
+    float mean, std;
+    int32_t lo, hi;
+    uint64_t seed;
+} exe_length_dist_t;
+int exe_profile(exe_model_t* m, int32_t phase, const int32_t* batch_sizes, int32_t n_batch,
+                const int32_t* lengths, int32_t n_len, const exe_length_dist_t* dist /* nullable */,
+                int32_t n_steps, exe_profile_row_t* rows, int32_t rows_cap, int32_t* n_rows);
+
+/*
+ * Per-kernel-class timing (HIP events on the model's stream around every launch of the class) with the
+ * algorithmic bytes and flops of those launches; used to report achieved GB/s or TFLOP/s.
+ * Enabling it serialises nothing but adds two event records per launch.
+ */
+enum { EXE_K_GEMM_TILE = 0, EXE_K_GEMM_SKINNY = 1, EXE_K_PREFILL_ATTN = 2, EXE_K_DECODE_ATTN = 3,
+       EXE_K_CROSS_ATTN = 4, EXE_K_NORM = 5, EXE_K_OTHER = 6, EXE_K_COUNT = 7 };
+typedef struct exe_kernel_time {
+    int32_t kind;
+    int64_t launches;
+    double ms;                     /* summed event time */
+    double bytes;                  /* algorithmic HBM bytes of those launches */
+    double flops;                  /* algorithmic flops of those launches */
+} exe_kernel_time_t;
+int exe_kernel_timing(exe_model_t* m, int32_t enable);           /* also resets the accumulators */
+int exe_kernel_times(exe_model_t* m, exe_kernel_time_t* rows /* [EXE_K_COUNT] */);
+
+/*
+ * Single-operation entry points (device pointers, enqueued on `hip_stream`, NOT synchronised).  They run
+ * the same kernels the model calls use; tests and micro-benchmarks call them.
+ */
+/* out = epilogue(alpha * A[M,K] . W[N,K]^T + bias):  out_mode 0: dtype out [M,N] with activation
+ * act (-1 none, EXE_ACT_*); 1: float resid [M,N] += result; 2: float out [M,N].
+ * workspace: float scratch of workspace_bytes (>= exe_op_gemm_workspace), may be NULL if that is 0. */
+int exe_op_gemm(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void* A,
+                const void* W, const void* bias, int32_t act, float alpha, int32_t out_mode, void* out,
+                void* workspace, uint64_t workspace_bytes);
+uint64_t exe_op_gemm_workspace(int32_t dtype, int32_t M, int32_t N, int32_t K);
+/* rows of float x [*, d] (row_index nullable selects rows) -> dtype out [rows, d] */
+int exe_op_norm(void* hip_stream, int32_t dtype, int32_t rms, const float* x, const int32_t* row_index,
+                int32_t rows, int32_t d, const void* gain, const void* shift, float eps, float out_scale,
+                void* out);
+/* Ragged prefill attention over packed qkv [T, 3*H*dh] (dtype): cu_seqlens [n_seqs+1] host.
+ * causal 0/1; bias_by_dist nullable device float [H, 2*bias_radius+1] indexed by clamp(key-query)+radius.
+ * out [T, H*dh] dtype. */
+int exe_op_prefill_attention(void* hip_stream, int32_t dtype, int32_t n_seqs, const int32_t* cu_seqlens,
+                             const void* qkv, int32_t H, int32_t dh, float scale, int32_t causal,
+                             const float* bias_by_dist, int32_t bias_radius, void* out, int32_t force_generic);
+/* Decode attention: q [B, H*dh] dtype; per sequence b the keys are at kv + k_offset[b] (elements) laid out
+ * [H][cap[b]][dh] and the values at kv + k_offset[b] + H*cap[b]*dh; len[b] keys are valid; the query's
+ * position is qpos[b] (for the bias only: index clamp(j - qpos)+radius).  All arrays device.  out [B, H*dh]. */
+int exe_op_decode_attention(void* hip_stream, int32_t dtype, int32_t B, const void* q, int32_t q_stride,
+                            const void* kv, const int64_t* k_offset, const int32_t* cap, const int32_t* len,
+                            const int32_t* qpos, int32_t H, int32_t dh, float scale,
+                            const float* bias_by_dist, int32_t bias_radius, void* out);
+/* argmax over each row of float logits [rows, n] -> int32 out [rows]; lowest index on ties */
+int exe_op_argmax(void* hip_stream, const float* logits, int32_t rows, int32_t n, int32_t* out);
+/* T5 bucket of rel = key - query as this library computes it (host function, exact integer arithmetic) */
+int exe_rel_bucket(int32_t rel, int32_t bidirectional, int32_t n_buckets, int32_t max_dist);
+
+const char* exe_last_error(void);
+const char* exe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

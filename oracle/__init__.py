@@ -32,7 +32,7 @@ def build(force: bool = False) -> None:
         if (not force and os.path.exists(out)
                 and os.path.getmtime(out) >= max(os.path.getmtime(_SRC), os.path.getmtime(_HDR))):
             continue
-        cmd = ["gcc", "-O3", "-march=native", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall",
+        cmd = ["gcc", "-O3", "-mavx2", "-mfma", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall",
                f"-DREAL={real}", "-o", out + ".tmp", _SRC, "-lm"]
         subprocess.run(cmd, check=True)
         os.replace(out + ".tmp", out)

@@ -1,0 +1,253 @@
+"""ctypes marshalling for include/exe.h.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_lib = None
+
+DECLARED_SYMBOLS = [
+    "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
+    "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_profile", "exe_kernel_timing",
+    "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_norm", "exe_op_prefill_attention",
+    "exe_op_decode_attention", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
+]
+KERNEL_KINDS = ["gemm_tile", "gemm_skinny", "prefill_attn", "decode_attn", "cross_attn", "norm", "other"]
+
+
+class ExeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"exe error {code}: {msg}")
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("arch", "n_layers", "n_dec_layers", "d_model", "n_heads", "head_dim", "d_ff", "vocab",
+                 "max_pos", "act", "norm", "pos", "rel_buckets", "rel_max_dist", "cross_rel_bias", "dtype",
+                 "has_embed", "has_lm_head", "scale_mode")] + \
+               [("norm_eps", C.c_float), ("kv_pool_bytes", C.c_uint64), ("max_seqs", C.c_int32),
+                ("max_batch_tokens", C.c_int32), ("max_batch_seqs", C.c_int32)]
+
+
+class Tensor(C.Structure):
+    _fields_ = [("ptr", C.c_void_p)]
+
+
+class ProfileRow(C.Structure):
+    _fields_ = [("phase", C.c_int32), ("batch", C.c_int32), ("length", C.c_int32), ("ragged", C.c_int32),
+                ("total_tokens", C.c_int32), ("attn_ms_per_layer", C.c_float), ("rest_ms_per_layer", C.c_float),
+                ("head_ms", C.c_float), ("full_step_ms", C.c_float), ("std_ms", C.c_float), ("n_timed", C.c_int32)]
+
+
+class LengthDist(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mean", C.c_float), ("std", C.c_float), ("lo", C.c_int32),
+                ("hi", C.c_int32), ("seed", C.c_uint64)]
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double),
+                ("flops", C.c_double)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libexe.so")
+
+
+def lib():
+    """Loads libexe.so.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    p = lib_path()
+    if not os.path.exists(p):
+        raise ImportError(f"{p} is not built; run `python -m paper_2404_07947_amd.build` (needs hipcc)")
+    L = C.CDLL(p)
+    vp, i32, ip = C.c_void_p, C.c_int32, C.POINTER(C.c_int32)
+    L.exe_expected_weights.argtypes = [C.POINTER(Config)]
+    L.exe_model_load.argtypes = [C.POINTER(Config), C.POINTER(Tensor), i32, vp, C.POINTER(vp)]
+    L.exe_model_free.argtypes = [vp]
+    L.exe_encode.argtypes = [vp, i32, ip, ip, ip, ip, vp, ip, vp]
+    L.exe_decode_step.argtypes = [vp, i32, ip, ip, ip, vp, ip, vp]
+    L.exe_seq_release.argtypes = [vp, i32, ip]
+    L.exe_seq_length.argtypes = [vp, i32]
+    L.exe_kv_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), ip]
+    L.exe_profile.argtypes = [vp, i32, ip, i32, ip, i32, C.POINTER(LengthDist), i32, C.POINTER(ProfileRow), i32, ip]
+    L.exe_kernel_timing.argtypes = [vp, i32]
+    L.exe_kernel_times.argtypes = [vp, C.POINTER(KernelTime)]
+    L.exe_op_gemm.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i32, C.c_float, i32, vp, vp, C.c_uint64]
+    L.exe_op_gemm_workspace.argtypes = [i32, i32, i32, i32]
+    L.exe_op_gemm_workspace.restype = C.c_uint64
+    L.exe_op_norm.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, C.c_float, C.c_float, vp]
+    L.exe_op_prefill_attention.argtypes = [vp, i32, i32, ip, vp, i32, i32, C.c_float, i32, vp, i32, vp, i32]
+    L.exe_op_decode_attention.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, vp, i32, vp]
+    L.exe_op_argmax.argtypes = [vp, vp, i32, i32, vp]
+    L.exe_rel_bucket.argtypes = [i32, i32, i32, i32]
+    L.exe_last_error.restype = C.c_char_p
+    L.exe_version.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise ExeError(rc, lib().exe_last_error().decode())
+    return rc
+
+
+def _i32(a) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ip(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _dev(t) -> Optional[int]:
+    """Device pointer of a torch tensor (or an int address), None for None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_cuda and t.is_contiguous(), "expected a contiguous device tensor"
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def config_from_shape(shape, kv_pool_bytes: int, max_seqs: int, max_batch_tokens: int, max_batch_seqs: int) -> Config:
+    """`shape` is any object with the ModelShape fields of the workload module."""
+    return Config(shape.arch, shape.n_layers, shape.n_dec_layers, shape.d_model, shape.n_heads, shape.head_dim,
+                  shape.d_ff, shape.vocab, shape.max_pos, shape.act, shape.norm, shape.pos, shape.rel_buckets,
+                  shape.rel_max_dist, shape.cross_rel_bias, shape.dtype, shape.has_embed, shape.has_lm_head,
+                  shape.scale_mode, shape.norm_eps, kv_pool_bytes, max_seqs, max_batch_tokens, max_batch_seqs)
+
+
+def exe_version() -> str:
+    return lib().exe_version().decode()
+
+
+def exe_rel_bucket(rel: int, bidirectional: int, n_buckets: int = 32, max_dist: int = 128) -> int:
+    return int(lib().exe_rel_bucket(rel, bidirectional, n_buckets, max_dist))
+
+
+class Model:
+    """Owns one exe_model_t.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, cfg: Config, weights: Sequence, stream=None):
+        L = lib()
+        self.cfg = cfg
+        self._weights = list(weights)           # keep the borrowed tensors alive
+        arr = (Tensor * len(self._weights))(*[Tensor(_dev(w)) for w in self._weights])
+        h = C.c_void_p()
+        self._stream = stream
+        _check(L.exe_model_load(C.byref(cfg), arr, len(self._weights), _stream_ptr(stream), C.byref(h)))
+        self._h = h
+
+    @staticmethod
+    def expected_weights(cfg: Config) -> int:
+        return _check(lib().exe_expected_weights(C.byref(cfg)))
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().exe_model_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def encode(self, seq_ids, input_lengths, tokens_packed=None, reserve_lengths=None, hidden_in=None,
+               want_tokens: bool = True, out_device=None) -> Optional[np.ndarray]:
+        ids, lens = _i32(seq_ids), _i32(input_lengths)
+        toks, res = _i32(tokens_packed), _i32(reserve_lengths)
+        nxt = np.zeros(len(ids), dtype=np.int32) if want_tokens else None
+        _check(lib().exe_encode(self._h, len(ids), _ip(ids), _ip(lens), _ip(toks), _ip(res), _dev(hidden_in),
+                                _ip(nxt), _dev(out_device)))
+        return nxt
+
+    def decode_step(self, seq_ids, tokens_in, kv_lengths, hidden_in=None, want_tokens: bool = True,
+                    out_device=None) -> Optional[np.ndarray]:
+        ids, toks, kvl = _i32(seq_ids), _i32(tokens_in), _i32(kv_lengths)
+        nxt = np.zeros(len(ids), dtype=np.int32) if want_tokens else None
+        _check(lib().exe_decode_step(self._h, len(ids), _ip(ids), _ip(toks), _ip(kvl), _dev(hidden_in), _ip(nxt),
+                                     _dev(out_device)))
+        return nxt
+
+    def seq_release(self, seq_ids) -> None:
+        ids = _i32(seq_ids)
+        _check(lib().exe_seq_release(self._h, len(ids), _ip(ids)))
+
+    def seq_length(self, seq_id: int) -> int:
+        return _check(lib().exe_seq_length(self._h, int(seq_id)))
+
+    def kv_stats(self) -> dict:
+        a, b, c, d = C.c_uint64(), C.c_uint64(), C.c_uint64(), C.c_int32()
+        _check(lib().exe_kv_stats(self._h, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
+        return {"pool_bytes": a.value, "used_bytes": b.value, "largest_free_bytes": c.value, "live_seqs": d.value}
+
+    def profile(self, phase: int, batch_sizes, lengths, dist: Optional[LengthDist] = None, n_steps: int = 20) -> List[dict]:
+        bs, ls = _i32(batch_sizes), _i32(lengths)
+        cap = len(bs) * len(ls)
+        rows = (ProfileRow * cap)()
+        n = C.c_int32()
+        _check(lib().exe_profile(self._h, phase, _ip(bs), len(bs), _ip(ls), len(ls),
+                                 C.byref(dist) if dist is not None else None, n_steps, rows, cap, C.byref(n)))
+        return [{f: getattr(rows[i], f) for f, _ in ProfileRow._fields_} for i in range(n.value)]
+
+    def kernel_timing(self, enable: bool) -> None:
+        _check(lib().exe_kernel_timing(self._h, int(enable)))
+
+    def kernel_times(self) -> List[dict]:
+        rows = (KernelTime * len(KERNEL_KINDS))()
+        _check(lib().exe_kernel_times(self._h, rows))
+        return [{"kind": KERNEL_KINDS[r.kind], "launches": r.launches, "ms": r.ms, "bytes": r.bytes, "flops": r.flops}
+                for r in rows]
+
+
+# ---- single-operation entry points (device tensors in, enqueued on the current torch stream) ----
+
+def exe_op_gemm_workspace(dtype: int, M: int, N: int, K: int) -> int:
+    return int(lib().exe_op_gemm_workspace(dtype, M, N, K))
+
+
+def exe_op_gemm(dtype, M, N, K, A, W, bias, act, alpha, out_mode, out, workspace=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().exe_op_gemm(_stream_ptr(stream), dtype, M, N, K, _dev(A), _dev(W), _dev(bias), act, alpha, out_mode,
+                             _dev(out), _dev(workspace), ws_bytes))
+
+
+def exe_op_norm(dtype, rms, x, row_index, rows, d, gain, shift, eps, out_scale, out, stream=None):
+    _check(lib().exe_op_norm(_stream_ptr(stream), dtype, rms, _dev(x), _dev(row_index), rows, d, _dev(gain),
+                             _dev(shift), eps, out_scale, _dev(out)))
+
+
+def exe_op_prefill_attention(dtype, cu_seqlens, qkv, H, dh, scale, causal, bias_by_dist, bias_radius, out,
+                             force_generic=0, stream=None):
+    cu = _i32(cu_seqlens)
+    _check(lib().exe_op_prefill_attention(_stream_ptr(stream), dtype, len(cu) - 1, _ip(cu), _dev(qkv), H, dh, scale,
+                                          causal, _dev(bias_by_dist), bias_radius, _dev(out), force_generic))
+
+
+def exe_op_decode_attention(dtype, B, q, q_stride, kv, k_offset, cap, length, qpos, H, dh, scale, bias_by_dist,
+                            bias_radius, out, stream=None):
+    _check(lib().exe_op_decode_attention(_stream_ptr(stream), dtype, B, _dev(q), q_stride, _dev(kv), _dev(k_offset),
+                                         _dev(cap), _dev(length), _dev(qpos), H, dh, scale, _dev(bias_by_dist),
+                                         bias_radius, _dev(out)))
+
+
+def exe_op_argmax(logits, rows, n, out, stream=None):
+    _check(lib().exe_op_argmax(_stream_ptr(stream), _dev(logits), rows, n, _dev(out)))

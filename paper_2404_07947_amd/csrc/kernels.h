@@ -1,0 +1,70 @@
+// Launchers of the gfx950 kernels.  All pointers are device pointers unless a comment says host.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace exe {
+
+struct GemmArgs {
+    int dtype;            // DT_F32 / DT_BF16: type of A, W, bias and (for OUT_T) out
+    int M, N, K;
+    const void* A;        // [M, K] row-major
+    const void* W;        // [N, K] row-major
+    const void* bias;     // [N] or nullptr
+    int act;              // -1 none, 0 relu, 1 gelu(erf); applied in OUT_T mode
+    float alpha;          // result = alpha * (A.W^T) + bias
+    int out_mode;         // OUT_T, OUT_RESID (float out += result), OUT_F32
+    void* out;            // [M, N]
+    float* workspace;     // split-K partial sums
+    size_t workspace_bytes;
+};
+size_t gemm_workspace_bytes(int dtype, int M, int N, int K);
+// which kernel family a shape runs on: 0 tile, 1 skinny, 2 generic
+int gemm_route(int dtype, int M, int N, int K);
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+hipError_t launch_embed(int dtype, const int32_t* tokens, const int32_t* pos, int T, int d, const void* tok_emb,
+                        const void* pos_emb, float* h, hipStream_t s);
+hipError_t launch_load_hidden(int dtype, const void* x, int64_t n, float* h, hipStream_t s);
+hipError_t launch_store_hidden(int dtype, const float* h, int64_t n, void* out, hipStream_t s);
+hipError_t launch_norm(int dtype, int rms, const float* x, const int32_t* row_index, int rows, int d,
+                       const void* gain, const void* shift, float eps, float out_scale, void* out, hipStream_t s);
+// copies K and V rows of `src` (row stride ld, K at column k_off, V at v_off) into the cache:
+// token t belongs to batch entry tok_b[t] (t itself if nullptr) at position tok_pos[t];
+// K of (b, head, pos) lives at pool + base[b] + ((layer*2+0)*H + head)*cap[b]*dh + pos*dh, V at kv index 1.
+hipError_t launch_kv_append(int dtype, const void* src, int ld, int k_off, int v_off, int T, const int32_t* tok_b,
+                            const int32_t* tok_pos, const int64_t* base, const int32_t* cap, int layer, int H, int dh,
+                            void* pool, hipStream_t s);
+hipError_t launch_argmax(const float* logits, int rows, int n, int32_t* out, hipStream_t s);
+
+struct AttnCacheArgs {       // one query row per batch entry against that sequence's cached K/V
+    int dtype, B, H, dh;
+    const void* q; int q_stride;          // q of (b, head) at q + b*q_stride + head*dh
+    const void* pool;
+    const int64_t* base; const int32_t* cap; const int32_t* len; const int32_t* qpos;
+    int layer;                             // K at base + ((layer*2)*H + head)*cap*dh
+    float scale;
+    const float* bias_by_dist; int bias_radius;   // [H, 2r+1] or nullptr
+    void* out;                             // [B, H*dh]
+};
+hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s);
+
+struct AttnPackedArgs {      // ragged prefill over packed qkv [T, 3*H*dh]
+    int dtype, T, H, dh, n_seqs;
+    const void* qkv;
+    const int32_t* tok_b;    // [T] sequence index of each token
+    const int32_t* tok_pos;  // [T] position in its sequence
+    const int32_t* cu;       // [n_seqs+1] first token of each sequence
+    int causal;
+    float scale;
+    const float* bias_by_dist; int bias_radius;
+    void* out;               // [T, H*dh]
+    // tile list for the MFMA kernel: (seq, first query row) pairs, longest work first
+    const int32_t* tiles; int n_tiles;
+    int force_generic;
+};
+bool prefill_mfma_supported(int dtype, int dh);
+constexpr int PREFILL_TILE_Q = 128;
+hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s);
+
+}  // namespace exe

@@ -1,0 +1,231 @@
+"""Per-kernel parity: each HIP kernel, called through the C ABI's exe_op_* entry points, against the
+oracle's primitive of the same operation on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2404_07947_amd as exe
+import workload as wl
+from gpu_util import DEV, relerr, row_relerr
+
+pytestmark = pytest.mark.gpu
+BF16, F32 = wl.DTYPE_BF16, wl.DTYPE_F32
+P = None
+
+
+def prim():
+    global P
+    if P is None:
+        P = oracle.Primitives("double")
+    return P
+
+
+def rnd(shape, seed, scale=1.0, dtype=torch.bfloat16):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(shape, generator=g) * scale).to(dtype)
+
+
+# ------------------------------------------------------------------ GEMM
+# (M, N, K): the shapes route to: skinny (M<=64), 128-tile with split-K, 128-tile, 256-tile, generic.
+GEMM_CASES = [
+    (1, 512, 512), (16, 5120, 5120), (17, 1024, 2560), (33, 2048, 512), (64, 15360, 5120), (50, 50272, 512),
+    (65, 512, 1024), (200, 1024, 512), (300, 640, 2048), (1000, 2048, 512),
+    (4099, 3072, 256), (2049, 6144, 128),
+    (37, 100, 72), (5, 52, 8),
+]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_CASES)
+@pytest.mark.parametrize("mode", ["act_relu", "act_gelu", "resid", "f32"])
+def test_gemm_bf16(M, N, K, mode):
+    if mode != "act_relu" and (M, N, K) in [(64, 15360, 5120), (50, 50272, 512), (4099, 3072, 256)]:
+        pytest.skip("large shapes run once")
+    print(f"gemm bf16 M={M} N={N} K={K} mode={mode} route={exe.lib().exe_op_gemm_workspace(BF16, M, N, K)}", flush=True)
+    A = rnd((M, K), 1, 1.0)
+    W = rnd((N, K), 2, 0.05)
+    b = rnd((N,), 3, 0.5)
+    Ad, Wd, bd = A.to(DEV), W.to(DEV), b.to(DEV)
+    ws_bytes = exe.exe_op_gemm_workspace(BF16, M, N, K)
+    ws = torch.empty(max(ws_bytes // 4, 1), dtype=torch.float32, device=DEV)
+    rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(M).integers(0, M, 6)]))
+    ref = prim().linear(A.float().numpy()[rows], W.float().numpy(), b.float().numpy())
+    alpha = 1.0
+    if mode == "act_relu" or mode == "act_gelu":
+        act = 0 if mode == "act_relu" else 1
+        out = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+        exe.exe_op_gemm(BF16, M, N, K, Ad, Wd, bd, act, alpha, 0, out, ws)
+        ref = prim().act(ref, act)
+        tol = 2.0 ** -8
+    elif mode == "resid":
+        h0 = rnd((M, N), 4, 1.0, torch.float32)
+        out = h0.to(DEV).clone()
+        exe.exe_op_gemm(BF16, M, N, K, Ad, Wd, bd, -1, alpha, 1, out, ws)
+        ref = ref + h0.numpy()[rows].astype(np.float64)
+        tol = 1e-5
+    else:
+        alpha = 0.37
+        ref = prim().linear(A.float().numpy()[rows] * 1.0, W.float().numpy(), None) * np.float64(np.float32(alpha)) \
+            + b.float().numpy().astype(np.float64)
+        out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        exe.exe_op_gemm(BF16, M, N, K, Ad, Wd, bd, -1, alpha, 2, out, ws)
+        tol = 1e-5
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()[rows]
+    # float accumulation of K products of magnitude <= ~|a||w|: error << tol * max|ref|
+    assert relerr(got, ref) < tol, (M, N, K, mode)
+
+
+@pytest.mark.parametrize("M,N,K", [(4, 2048, 256), (37, 1024, 256), (100, 768, 1024), (3, 52, 24)])
+def test_gemm_f32(M, N, K):
+    A = rnd((M, K), 5, 1.0, torch.float32)
+    W = rnd((N, K), 6, 0.05, torch.float32)
+    b = rnd((N,), 7, 0.5, torch.float32)
+    out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    exe.exe_op_gemm(F32, M, N, K, A.to(DEV), W.to(DEV), b.to(DEV), 1, 1.0, 0, out, None)
+    torch.cuda.synchronize()
+    ref = prim().act(prim().linear(A.numpy(), W.numpy(), b.numpy()), 1)
+    assert relerr(out.cpu().numpy(), ref) < 2e-6
+
+
+def test_gemm_no_bias_and_determinism():
+    M, N, K = 48, 5120, 20480            # skinny with split-K
+    A, W = rnd((M, K), 8), rnd((N, K), 9, 0.02)
+    Ad, Wd = A.to(DEV), W.to(DEV)
+    ws = torch.empty(exe.exe_op_gemm_workspace(BF16, M, N, K) // 4 + 1, dtype=torch.float32, device=DEV)
+    outs = []
+    for _ in range(2):
+        out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        exe.exe_op_gemm(BF16, M, N, K, Ad, Wd, None, -1, 1.0, 2, out, ws)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])       # fixed summation order: bitwise reproducible
+    rows = [0, 15, 16, 47]
+    ref = prim().linear(A.float().numpy()[rows], W.float().numpy(), None)
+    assert relerr(outs[0][rows], ref) < 1e-5
+
+
+# ------------------------------------------------------------------ norms
+@pytest.mark.parametrize("dtype", [BF16, F32])
+@pytest.mark.parametrize("rms", [0, 1])
+@pytest.mark.parametrize("d", [256, 5120, 12288])
+def test_norm(dtype, rms, d):
+    td = torch.float32 if dtype == F32 else torch.bfloat16
+    rows = 7
+    x = rnd((11, d), 10, 3.0, torch.float32) + 0.7
+    g = (1 + rnd((d,), 11, 0.1, torch.float32)).to(td)
+    b = rnd((d,), 12, 0.1, torch.float32).to(td)
+    idx = torch.tensor([10, 0, 3, 3, 7, 1, 9], dtype=torch.int32)
+    out = torch.zeros((rows, d), dtype=td, device=DEV)
+    eps = 1e-6 if rms else 1e-5
+    exe.exe_op_norm(dtype, rms, x.to(DEV), idx.to(DEV), rows, d, g.to(DEV), b.to(DEV), eps, 0.5, out)
+    torch.cuda.synchronize()
+    xs = x.numpy()[idx.numpy()]
+    e = float(np.float32(eps))
+    ref = (prim().rmsnorm(xs, g.float().numpy(), e) if rms else
+           prim().layernorm(xs, g.float().numpy(), b.float().numpy(), e)) * 0.5
+    assert relerr(out.float().cpu().numpy(), ref) < (2e-6 if dtype == F32 else 2.0 ** -8)
+
+
+# ------------------------------------------------------------------ argmax
+def test_argmax_lowest_index_on_ties():
+    n = 50272
+    x = rnd((5, n), 13, 1.0, torch.float32)
+    x[1, 40000] = 9.0; x[1, 123] = 9.0; x[1, 50271] = 9.0
+    x[2, :] = 0.25
+    x[3, n - 1] = 7.0
+    x[4, 0] = 7.0
+    out = torch.zeros(5, dtype=torch.int32, device=DEV)
+    exe.exe_op_argmax(x.to(DEV), 5, n, out)
+    torch.cuda.synchronize()
+    want = [prim().argmax(x[i].numpy()) for i in range(5)]
+    assert out.cpu().tolist() == want
+    assert want[1:] == [123, 0, n - 1, 0]
+
+
+# ------------------------------------------------------------------ attention
+def oracle_attention(q, K, V, scale, bias=None):
+    return prim().attention_row(q, K, V, scale, bias)[0]
+
+
+def bias_table(H, R, seed):
+    """Arbitrary per-head table over clamped distances (the kernel only indexes it)."""
+    return rnd((H, 2 * R + 1), seed, 0.5, torch.float32)
+
+
+@pytest.mark.parametrize("dtype,dh,H", [(BF16, 128, 5), (BF16, 64, 3), (F32, 64, 4), (F32, 128, 2)])
+@pytest.mark.parametrize("use_bias", [0, 1])
+def test_decode_attention(dtype, dh, H, use_bias):
+    td = torch.float32 if dtype == F32 else torch.bfloat16
+    lens = [1, 2, 63, 64, 65, 300, 1023, 17]
+    B = len(lens)
+    caps = [((L + 9) // 8) * 8 for L in lens]
+    offs, tot = [], 0
+    for c in caps:
+        offs.append(tot)
+        tot += 2 * H * c * dh + 64        # gaps between extents
+    pool = rnd((tot,), 14, 1.0, td)
+    q = rnd((B, H * dh), 15, 1.0, td)
+    R = 128
+    tab = bias_table(H, R, 16) if use_bias else None
+    qpos = [L - 1 for L in lens]
+    qpos[5] = 40                            # cross-attention style: query position unrelated to the length
+    out = torch.zeros((B, H * dh), dtype=td, device=DEV)
+    i64 = lambda a: torch.tensor(a, dtype=torch.int64, device=DEV)
+    i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=DEV)
+    scale = 1.0 / np.sqrt(dh)
+    exe.exe_op_decode_attention(dtype, B, q.to(DEV), H * dh, pool.to(DEV), i64(offs), i32(caps), i32(lens), i32(qpos),
+                                H, dh, scale, None if tab is None else tab.to(DEV), R, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    pf = pool.float().numpy()
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            kb = offs[b] + h * caps[b] * dh
+            K = pf[kb: kb + lens[b] * dh].reshape(lens[b], dh)
+            vb = offs[b] + H * caps[b] * dh + h * caps[b] * dh
+            V = pf[vb: vb + lens[b] * dh].reshape(lens[b], dh)
+            bias = None
+            if use_bias:
+                rel = np.clip(np.arange(lens[b]) - qpos[b], -R, R) + R
+                bias = tab.numpy()[h][rel]
+            ref = oracle_attention(q.float().numpy()[b, h * dh:(h + 1) * dh], K, V, float(np.float32(scale)), bias)
+            worst = max(worst, relerr(got[b, h * dh:(h + 1) * dh], ref))
+    assert worst < (1e-5 if dtype == F32 else 2.0 ** -7), worst
+
+
+@pytest.mark.parametrize("dtype,dh,H,generic", [(BF16, 128, 3, 0), (BF16, 128, 3, 1), (BF16, 64, 2, 0), (F32, 64, 4, 0)])
+@pytest.mark.parametrize("causal,use_bias", [(1, 0), (0, 1), (1, 1), (0, 0)])
+def test_prefill_attention(dtype, dh, H, generic, causal, use_bias):
+    td = torch.float32 if dtype == F32 else torch.bfloat16
+    lens = [1, 127, 128, 129, 300, 64, 5]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    inner = H * dh
+    qkv = rnd((T, 3 * inner), 17, 1.0, td)
+    R = 128
+    tab = bias_table(H, R, 18) if use_bias else None
+    out = torch.zeros((T, inner), dtype=td, device=DEV)
+    scale = 1.0 / np.sqrt(dh) if causal else 0.11
+    exe.exe_op_prefill_attention(dtype, cu, qkv.to(DEV), H, dh, scale, causal, None if tab is None else tab.to(DEV), R,
+                                 out, force_generic=generic)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    x = qkv.float().numpy()
+    rng = np.random.default_rng(19)
+    worst = 0.0
+    for s, L in enumerate(lens):
+        for i in sorted(set([0, L - 1] + list(rng.integers(0, L, 4)))):
+            for h in range(H):
+                t = cu[s] + i
+                nk = i + 1 if causal else L
+                K = x[cu[s]: cu[s] + nk, inner + h * dh: inner + (h + 1) * dh]
+                V = x[cu[s]: cu[s] + nk, 2 * inner + h * dh: 2 * inner + (h + 1) * dh]
+                bias = None
+                if use_bias:
+                    bias = tab.numpy()[h][np.clip(np.arange(nk) - i, -R, R) + R]
+                ref = oracle_attention(x[t, h * dh:(h + 1) * dh], K, V, float(np.float32(scale)), bias)
+                worst = max(worst, relerr(got[t, h * dh:(h + 1) * dh], ref))
+    # bf16: probabilities are rounded to bf16 before the second product in the MFMA kernel
+    assert worst < (1e-5 if dtype == F32 else 2.0 ** -6), worst
