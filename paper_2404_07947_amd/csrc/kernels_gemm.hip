@@ -54,16 +54,22 @@ constexpr int BK = 64;   // bf16 elements along K per LDS stage: one 128-byte ro
 // A 16-lane group reading the same chunk of 16 consecutive rows then touches 16 distinct 16-byte bank groups.
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+
+// Tiles are filled with direct global->LDS loads (no staging registers): one wave-wide 16-byte load
+// writes 1 KB = 8 consecutive tile rows, lane l landing at byte 16*l.  The swizzle is therefore applied on
+// the global side: lane l fetches chunk (l%8) ^ key(row) of row l/8.
 template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias,
     int act, float alpha, int out_mode, void* __restrict__ out, float* __restrict__ partial, int tiles_m, int tiles_n,
     int k_per_split)
 {
-    constexpr int NT = (BM / WM) * (BN / WN) * 64;
+    constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_PASSES = BM * 8 / NT, B_PASSES = BN * 8 / NT;   // 16-byte chunks per thread per stage
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
+    constexpr int A_PASSES = BM / 8 / NW, B_PASSES = BN / 8 / NW;   // 1 KB wave-loads per wave per stage
+    static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "tile/waves mismatch");
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int STAGE = (BM + BN) * 128;   // bytes per LDS stage: A tile then W tile
 
@@ -87,29 +93,32 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int wm = wave % (BM / WM), wn = wave / (BM / WM);
-    int ld_chunk = tid & 7, ld_row = tid >> 3;      // NT/8 rows per pass
 
-    uint4 ra[A_PASSES], rb[B_PASSES];
-    auto load_global = [&](int kt) {
-        int k = kbeg + kt * BK + ld_chunk * 8;
+    // per-lane global source of each wave-load (row clamped into the matrix; rows past the edge are never stored)
+    const bf16_t* src_a[A_PASSES];
+    const bf16_t* src_w[B_PASSES];
 #pragma unroll
-        for (int p = 0; p < A_PASSES; ++p) {
-            int r = m0 + ld_row + p * (NT / 8);
-            r = r < M ? r : M - 1;
-            ra[p] = *(const uint4*)(A + (int64_t)r * K + k);
-        }
+    for (int p = 0; p < A_PASSES; ++p) {
+        int rl = (p * NW + wave) * 8 + (lane >> 3);
+        int r = m0 + rl;
+        r = r < M ? r : M - 1;
+        src_a[p] = A + (int64_t)r * K + kbeg + (((lane & 7) ^ ((rl >> 1) & 7)) << 3);
+    }
 #pragma unroll
-        for (int p = 0; p < B_PASSES; ++p) {
-            int r = n0 + ld_row + p * (NT / 8);
-            r = r < N ? r : N - 1;
-            rb[p] = *(const uint4*)(W + (int64_t)r * K + k);
-        }
-    };
-    auto store_lds = [&](int buf) {
+    for (int p = 0; p < B_PASSES; ++p) {
+        int rl = (p * NW + wave) * 8 + (lane >> 3);
+        int r = n0 + rl;
+        r = r < N ? r : N - 1;
+        src_w[p] = W + (int64_t)r * K + kbeg + (((lane & 7) ^ ((rl >> 1) & 7)) << 3);
+    }
+    auto issue_loads = [&](int kt, int buf) {
+        unsigned char* base = lds + buf * STAGE;
 #pragma unroll
-        for (int p = 0; p < A_PASSES; ++p) *(uint4*)(lds + buf * STAGE + lds_off(ld_row + p * (NT / 8), ld_chunk)) = ra[p];
+        for (int p = 0; p < A_PASSES; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_a[p] + kt * BK), (lds_ptr_t)(base + (p * NW + wave) * 1024), 16, 0, 0);
 #pragma unroll
-        for (int p = 0; p < B_PASSES; ++p) *(uint4*)(lds + buf * STAGE + BM * 128 + lds_off(ld_row + p * (NT / 8), ld_chunk)) = rb[p];
+        for (int p = 0; p < B_PASSES; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_w[p] + kt * BK), (lds_ptr_t)(base + BM * 128 + (p * NW + wave) * 1024), 16, 0, 0);
     };
 
     f32x16 acc[TN][TM];
@@ -120,27 +129,29 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    load_global(0);
-    store_lds(0);
+    issue_loads(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-bound loads have landed
     __syncthreads();
     int frow = lane & 31, fk = lane >> 5;
     for (int kt = 0; kt < nk; ++kt) {
         int buf = kt & 1;
-        if (kt + 1 < nk) load_global(kt + 1);
+        if (kt + 1 < nk) issue_loads(kt + 1, buf ^ 1);
+        const unsigned char* sa = lds + buf * STAGE;
+        const unsigned char* sw = sa + BM * 128;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fa[TM], fw[TN];
 #pragma unroll
-            for (int j = 0; j < TM; ++j) fa[j] = *(const bf16x8*)(lds + buf * STAGE + lds_off(wm * WM + j * 32 + frow, ks * 2 + fk));
+            for (int j = 0; j < TM; ++j) fa[j] = *(const bf16x8*)(sa + lds_off(wm * WM + j * 32 + frow, ks * 2 + fk));
 #pragma unroll
-            for (int i = 0; i < TN; ++i) fw[i] = *(const bf16x8*)(lds + buf * STAGE + BM * 128 + lds_off(wn * WN + i * 32 + frow, ks * 2 + fk));
+            for (int i = 0; i < TN; ++i) fw[i] = *(const bf16x8*)(sw + lds_off(wn * WN + i * 32 + frow, ks * 2 + fk));
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) store_lds(buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
     }
 
@@ -400,12 +411,12 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         size_t lds = 2 * (256 + 256) * 128;
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<256, 256, 128, 128>,
+            hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<256, 256, 128, 64>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        gemm_tile_kernel<256, 256, 128, 128><<<dim3(tm * tn, 1, p.splits), 256, lds, s>>>(
+        gemm_tile_kernel<256, 256, 128, 64><<<dim3(tm * tn, 1, p.splits), 512, lds, s>>>(
             a.M, a.N, a.K, A, W, bias, a.act, a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split);
     } else {
         int tm = (a.M + 127) / 128, tn = (a.N + 127) / 128;
