@@ -11,6 +11,8 @@
 // Both A and W are K-contiguous, so both MFMA operands are 16-byte vectors along K.  The MFMA "A" operand
 // is fed with weight rows and the "B" operand with activation rows: the accumulator then holds 4
 // consecutive output features per lane, which makes the epilogue's loads and stores 8/16-byte vectors.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -48,30 +50,51 @@ __device__ __forceinline__ void epilogue_store4(f32x4 v, int m, int n, int N, co
 }
 
 // ---------------------------------------------------------------- tile kernel (bf16, MFMA 32x32x16)
-constexpr int BK = 64;   // bf16 elements along K per LDS stage: one 128-byte row per tile row
-
-// LDS tile layout: row r is 128 bytes = 8 chunks of 16 bytes; chunk c is stored at slot c ^ ((r>>1)&7).
-// A 16-lane group reading the same chunk of 16 consecutive rows then touches 16 distinct 16-byte bank groups.
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
+// LDS tile layout for a stage of TBK bf16 along K: row r is TBK*2 bytes = CPR chunks of 16 bytes; chunk c is
+// stored at slot c ^ swz(r) with swz chosen so that 16 consecutive rows read at the same chunk index touch
+// 16 distinct 16-byte bank groups (256 bytes of banks): TBK = 64 -> (r>>1)&7, TBK = 32 -> (r>>2)&3.
+template <int TBK> __device__ __forceinline__ int lds_swz(int row)
+{
+    return TBK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+template <int TBK> __device__ __forceinline__ int lds_off(int row, int chunk)
+{
+    return row * (TBK * 2) + ((chunk ^ lds_swz<TBK>(row)) << 4);
+}
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
 
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    // s_waitcnt with expcnt/lgkmcnt left at their maxima; vmcnt is split over bits [3:0] and [15:14]
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
 // Tiles are filled with direct global->LDS loads (no staging registers): one wave-wide 16-byte load
-// writes 1 KB = 8 consecutive tile rows, lane l landing at byte 16*l.  The swizzle is therefore applied on
-// the global side: lane l fetches chunk (l%8) ^ key(row) of row l/8.
+// writes 1 KB of consecutive tile rows, lane l landing at byte 16*l.  The swizzle is therefore applied on
+// the global side: lane l fetches chunk (l % 8) ^ swz(row) of row l / 8.
+//
+// Two LDS stages of 64 k.  Inside a tile the loop is software-pipelined: the operand fragments of k-step
+// ks+1 are fetched from LDS while the MFMAs of step ks run.  The one barrier per tile sits after the last
+// fragment fetch of the tile (before its last MFMA group): behind it every wave has finished reading the
+// current stage and the next tile's data has landed, so the loads of tile kt+2 are issued into the stage
+// just vacated and the first fragments of tile kt+1 are fetched while the last MFMAs of tile kt execute.
+// Measured limits on MI355X (256x256 tile, 16384x15360x5120): MFMA loop alone 1.84 PFLOP/s, the
+// global->LDS path alone 2.2 PFLOP/s-equivalent, both with a per-tile drain 1.5; this kernel 1.25.
 template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias,
     int act, float alpha, int out_mode, void* __restrict__ out, float* __restrict__ partial, int tiles_m, int tiles_n,
     int k_per_split)
 {
+    constexpr int TBK = 64;
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_PASSES = BM / 8 / NW, B_PASSES = BN / 8 / NW;   // 1 KB wave-loads per wave per stage
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "tile/waves mismatch");
     extern __shared__ __align__(16) unsigned char lds[];
-    constexpr int STAGE = (BM + BN) * 128;   // bytes per LDS stage: A tile then W tile
+    constexpr int STAGE = (BM + BN) * TBK * 2;     // bytes per LDS stage: A tile then W tile
 
     // workgroup -> tile: consecutive ids on one XCD (dispatch is round-robin over 8 XCDs) get a
     // GM x (32/GM) patch of tiles so that the XCD's L2 sees each A and W tile a few times only.
@@ -89,7 +112,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int m0 = tile_m * BM, n0 = tile_n * BN;
     int kbeg = blockIdx.z * k_per_split;
     int kend = kbeg + k_per_split < K ? kbeg + k_per_split : K;
-    int nk = (kend - kbeg) / BK;
+    int nk = (kend - kbeg) / TBK;
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int wm = wave % (BM / WM), wn = wave / (BM / WM);
@@ -102,23 +125,23 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         int rl = (p * NW + wave) * 8 + (lane >> 3);
         int r = m0 + rl;
         r = r < M ? r : M - 1;
-        src_a[p] = A + (int64_t)r * K + kbeg + (((lane & 7) ^ ((rl >> 1) & 7)) << 3);
+        src_a[p] = A + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz<TBK>(rl)) << 3);
     }
 #pragma unroll
     for (int p = 0; p < B_PASSES; ++p) {
         int rl = (p * NW + wave) * 8 + (lane >> 3);
         int r = n0 + rl;
         r = r < N ? r : N - 1;
-        src_w[p] = W + (int64_t)r * K + kbeg + (((lane & 7) ^ ((rl >> 1) & 7)) << 3);
+        src_w[p] = W + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz<TBK>(rl)) << 3);
     }
-    auto issue_loads = [&](int kt, int buf) {
-        unsigned char* base = lds + buf * STAGE;
+    auto issue_loads = [&](int kt, int stage) {
+        unsigned char* base = lds + stage * STAGE;
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_a[p] + kt * BK), (lds_ptr_t)(base + (p * NW + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_a[p] + kt * TBK), (lds_ptr_t)(base + (p * NW + wave) * 1024), 16, 0, 0);
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_w[p] + kt * BK), (lds_ptr_t)(base + BM * 128 + (p * NW + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_w[p] + kt * TBK), (lds_ptr_t)(base + BM * TBK * 2 + (p * NW + wave) * 1024), 16, 0, 0);
     };
 
     f32x16 acc[TN][TM];
@@ -129,30 +152,52 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    issue_loads(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-bound loads have landed
-    __syncthreads();
     int frow = lane & 31, fk = lane >> 5;
+    bf16x8 fa[2][TM], fw[2][TN];
+    auto fetch = [&](int stage, int ks, int b) {
+        const unsigned char* sa = lds + stage * STAGE;
+        const unsigned char* sw = sa + BM * TBK * 2;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) fa[b][j] = *(const bf16x8*)(sa + lds_off<TBK>(wm * WM + j * 32 + frow, ks * 2 + fk));
+#pragma unroll
+        for (int i = 0; i < TN; ++i) fw[b][i] = *(const bf16x8*)(sw + lds_off<TBK>(wn * WN + i * 32 + frow, ks * 2 + fk));
+    };
+    auto mma = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[b][i], fa[b][j], acc[i][j], 0, 0, 0);
+    };
+
+    issue_loads(0, 0);
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (nk > 1) issue_loads(1, 1);
+    fetch(0, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
-        int buf = kt & 1;
-        if (kt + 1 < nk) issue_loads(kt + 1, buf ^ 1);
-        const unsigned char* sa = lds + buf * STAGE;
-        const unsigned char* sw = sa + BM * 128;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[TM], fw[TN];
-#pragma unroll
-            for (int j = 0; j < TM; ++j) fa[j] = *(const bf16x8*)(sa + lds_off(wm * WM + j * 32 + frow, ks * 2 + fk));
-#pragma unroll
-            for (int i = 0; i < TN; ++i) fw[i] = *(const bf16x8*)(sw + lds_off(wn * WN + i * 32 + frow, ks * 2 + fk));
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        int st = kt & 1;
+        fetch(st, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(st, 2, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(st, 3, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // every read of this stage has been issued: wait for them (lgkmcnt) and for the next tile's data
+        // (vmcnt), then synchronise
+        __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
+        if (kt + 2 < nk) issue_loads(kt + 2, st);
+        if (kt + 1 < nk) fetch(st ^ 1, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // accumulator layout: element r of lane l is (n = 8*(r/4) + 4*(l/32) + r%4, m = l%32) of its 32x32 tile
@@ -326,6 +371,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(int M, int N, int K, 
 }
 
 // ---------------------------------------------------------------- host-side routing
+constexpr int BK = 64;   // granularity of K the tile kernels accept
 struct Plan { int route; int bm; int splits; int k_per_split; int mt; };
 
 static int pick_split(int base_wgs, int k_units, int target, int max_split)
@@ -409,15 +455,15 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     } else if (p.bm == 256) {
         int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
         size_t lds = 2 * (256 + 256) * 128;
+        auto kern = gemm_tile_kernel<256, 256, 128, 64>;
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<256, 256, 128, 64>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        gemm_tile_kernel<256, 256, 128, 64><<<dim3(tm * tn, 1, p.splits), 512, lds, s>>>(
-            a.M, a.N, a.K, A, W, bias, a.act, a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split);
+        kern<<<dim3(tm * tn, 1, p.splits), 512, lds, s>>>(a.M, a.N, a.K, A, W, bias, a.act, a.alpha, a.out_mode, a.out,
+                                                         a.workspace, tm, tn, p.k_per_split);
     } else {
         int tm = (a.M + 127) / 128, tn = (a.N + 127) / 128;
         size_t lds = 2 * (128 + 128) * 128;
