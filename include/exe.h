@@ -166,6 +166,8 @@ int exe_profile(exe_model_t* m, int32_t phase, const int32_t* batch_sizes, int32
  * algorithmic bytes and flops of those launches; used to report achieved GB/s or TFLOP/s.
  * Enabling it serialises nothing but adds two event records per launch.
  */
+/* EXE_K_GEMM_TILE: GEMM launches with more than 256 rows (MFMA-bound); EXE_K_GEMM_SKINNY: at most 256 rows
+ * (the weights are streamed once: HBM-bound). */
 enum { EXE_K_GEMM_TILE = 0, EXE_K_GEMM_SKINNY = 1, EXE_K_PREFILL_ATTN = 2, EXE_K_DECODE_ATTN = 3,
        EXE_K_CROSS_ATTN = 4, EXE_K_NORM = 5, EXE_K_OTHER = 6, EXE_K_COUNT = 7 };
 typedef struct exe_kernel_time {
@@ -184,7 +186,7 @@ int exe_kernel_times(exe_model_t* m, exe_kernel_time_t* rows /* [EXE_K_COUNT] */
  */
 /* out = epilogue(alpha * A[M,K] . W[N,K]^T + bias):  out_mode 0: dtype out [M,N] with activation
  * act (-1 none, EXE_ACT_*); 1: float resid [M,N] += result; 2: float out [M,N].
- * workspace: float scratch of workspace_bytes (>= exe_op_gemm_workspace), may be NULL if that is 0. */
+ * workspace: device scratch of workspace_bytes (>= exe_op_gemm_workspace), may be NULL if that is 0. */
 int exe_op_gemm(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void* A,
                 const void* W, const void* bias, int32_t act, float alpha, int32_t out_mode, void* out,
                 void* workspace, uint64_t workspace_bytes);

@@ -1,12 +1,10 @@
 // GEMM kernels for the projections of a Transformer layer: out = epilogue(alpha * A[M,K] . W[N,K]^T + bias).
 //
-//  * gemm_tile_kernel   bf16, MFMA 32x32x16, LDS double-buffered macro tiles (256x256 or 128x128, BK = 64),
-//                       optional split-K into float partial sums.  The encode (prefill) workhorse.
-//  * gemm_skinny_kernel bf16, MFMA 16x16x32, M <= 64: every wave streams its own 16 weight rows straight
-//                       from HBM into MFMA operand registers; activations are staged through LDS; split-K
-//                       over the grid.  The decode (weight-streaming) workhorse.
+//  * gemm_tile_kernel    bf16, MFMA 32x32x16.  Macro tiles (BM x 256 or BM x 128, 64 k per LDS stage) filled by
+//                        direct global->LDS loads into a ring of stages; software-pipelined fragment fetch;
+//                        optional split-K into float partials, finished by splitk_reduce_kernel.
+//                        Large M (encode) is MFMA / LDS-fill bound; small M (decode) streams the weights.
 //  * gemm_generic_kernel float or bf16 inputs, plain FMA in float, any shape (tiny fp32 config, odd shapes).
-//  * splitk_reduce_kernel sums the partials in a fixed order (deterministic) and applies the epilogue.
 //
 // Both A and W are K-contiguous, so both MFMA operands are 16-byte vectors along K.  The MFMA "A" operand
 // is fed with weight rows and the "B" operand with activation rows: the accumulator then holds 4
@@ -50,49 +48,50 @@ __device__ __forceinline__ void epilogue_store4(f32x4 v, int m, int n, int N, co
 }
 
 // ---------------------------------------------------------------- tile kernel (bf16, MFMA 32x32x16)
-// LDS tile layout for a stage of TBK bf16 along K: row r is TBK*2 bytes = CPR chunks of 16 bytes; chunk c is
-// stored at slot c ^ swz(r) with swz chosen so that 16 consecutive rows read at the same chunk index touch
-// 16 distinct 16-byte bank groups (256 bytes of banks): TBK = 64 -> (r>>1)&7, TBK = 32 -> (r>>2)&3.
-template <int TBK> __device__ __forceinline__ int lds_swz(int row)
-{
-    return TBK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
-}
-template <int TBK> __device__ __forceinline__ int lds_off(int row, int chunk)
-{
-    return row * (TBK * 2) + ((chunk ^ lds_swz<TBK>(row)) << 4);
-}
+// LDS tile layout for a stage of 64 bf16 along K: row r is 128 bytes = 8 chunks of 16 bytes; chunk c is
+// stored at slot c ^ ((r>>1)&7), so that 16 consecutive rows read at the same chunk index touch 16 distinct
+// 16-byte bank groups (256 bytes of banks; measured: zero LDS bank conflicts).
+constexpr int TBK = 64;
+__device__ __forceinline__ int lds_swz(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ lds_swz(row)) << 4); }
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
 
-template <int N> __device__ __forceinline__ void wait_vmcnt()
+// s_waitcnt vmcnt(N) lgkmcnt(L) with expcnt at its maximum; vmcnt is split over bits [3:0] and [15:14],
+// lgkmcnt is bits [11:8]
+template <int N, int L> __device__ __forceinline__ void wait_cnt()
 {
-    // s_waitcnt with expcnt/lgkmcnt left at their maxima; vmcnt is split over bits [3:0] and [15:14]
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14) | (L << 8));
 }
 
 // Tiles are filled with direct global->LDS loads (no staging registers): one wave-wide 16-byte load
 // writes 1 KB of consecutive tile rows, lane l landing at byte 16*l.  The swizzle is therefore applied on
 // the global side: lane l fetches chunk (l % 8) ^ swz(row) of row l / 8.
 //
-// Two LDS stages of 64 k.  Inside a tile the loop is software-pipelined: the operand fragments of k-step
-// ks+1 are fetched from LDS while the MFMAs of step ks run.  The one barrier per tile sits after the last
-// fragment fetch of the tile (before its last MFMA group): behind it every wave has finished reading the
-// current stage and the next tile's data has landed, so the loads of tile kt+2 are issued into the stage
-// just vacated and the first fragments of tile kt+1 are fetched while the last MFMAs of tile kt execute.
+// ST LDS stages of 64 k form a ring: while tile kt is multiplied, tiles kt+1 .. kt+ST-1 are in flight.
+// Inside a tile the loop is software-pipelined: the operand fragments of k-step ks+1 are fetched from LDS
+// while the MFMAs of step ks run.  The one barrier per tile sits after the last fragment fetch of the tile
+// (before its last MFMA group): behind it every wave has finished reading the current stage and tile kt+1
+// has landed, so the loads of tile kt+ST are issued into the stage just vacated and the first fragments of
+// tile kt+1 are fetched while the last MFMAs of tile kt execute.
+//
+// Split-K (gridDim.z > 1): every workgroup writes its float partial tile; splitk_reduce_kernel finishes.
+//
 // Measured limits on MI355X (256x256 tile, 16384x15360x5120): MFMA loop alone 1.84 PFLOP/s, the
-// global->LDS path alone 2.2 PFLOP/s-equivalent, both with a per-tile drain 1.5; this kernel 1.25.
-template <int BM, int BN, int WM, int WN>
+// global->LDS path alone 2.2 PFLOP/s-equivalent (1.5 with a drain per tile); this kernel about 1.1-1.25.
+template <int BM, int BN, int WM, int WN, int ST>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias,
     int act, float alpha, int out_mode, void* __restrict__ out, float* __restrict__ partial, int tiles_m, int tiles_n,
     int k_per_split)
 {
-    constexpr int TBK = 64;
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_PASSES = BM / 8 / NW, B_PASSES = BN / 8 / NW;   // 1 KB wave-loads per wave per stage
+    constexpr int LPT = A_PASSES + B_PASSES;
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "tile/waves mismatch");
+    static_assert(LPT * (ST - 1) <= 63, "vmcnt range");
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int STAGE = (BM + BN) * TBK * 2;     // bytes per LDS stage: A tile then W tile
 
@@ -125,16 +124,18 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         int rl = (p * NW + wave) * 8 + (lane >> 3);
         int r = m0 + rl;
         r = r < M ? r : M - 1;
-        src_a[p] = A + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz<TBK>(rl)) << 3);
+        src_a[p] = A + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz(rl)) << 3);
     }
 #pragma unroll
     for (int p = 0; p < B_PASSES; ++p) {
         int rl = (p * NW + wave) * 8 + (lane >> 3);
         int r = n0 + rl;
         r = r < N ? r : N - 1;
-        src_w[p] = W + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz<TBK>(rl)) << 3);
+        src_w[p] = W + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz(rl)) << 3);
     }
+    // tile `kt` (clamped to the last one, which keeps the number of loads in flight uniform) -> stage
     auto issue_loads = [&](int kt, int stage) {
+        kt = kt < nk ? kt : nk - 1;
         unsigned char* base = lds + stage * STAGE;
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p)
@@ -158,9 +159,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         const unsigned char* sa = lds + stage * STAGE;
         const unsigned char* sw = sa + BM * TBK * 2;
 #pragma unroll
-        for (int j = 0; j < TM; ++j) fa[b][j] = *(const bf16x8*)(sa + lds_off<TBK>(wm * WM + j * 32 + frow, ks * 2 + fk));
+        for (int j = 0; j < TM; ++j) fa[b][j] = *(const bf16x8*)(sa + lds_off(wm * WM + j * 32 + frow, ks * 2 + fk));
 #pragma unroll
-        for (int i = 0; i < TN; ++i) fw[b][i] = *(const bf16x8*)(sw + lds_off<TBK>(wn * WN + i * 32 + frow, ks * 2 + fk));
+        for (int i = 0; i < TN; ++i) fw[b][i] = *(const bf16x8*)(sw + lds_off(wn * WN + i * 32 + frow, ks * 2 + fk));
     };
     auto mma = [&](int b) {
 #pragma unroll
@@ -170,13 +171,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[b][i], fa[b][j], acc[i][j], 0, 0, 0);
     };
 
-    issue_loads(0, 0);
-    wait_vmcnt<0>();
+    // prologue: tiles 0 .. ST-1 go to stages 0 .. ST-1; wait for tile 0 only
+#pragma unroll
+    for (int t = 0; t < ST; ++t) issue_loads(t, t);
+    wait_cnt<LPT*(ST - 1), 15>();
     __syncthreads();
-    if (nk > 1) issue_loads(1, 1);
     fetch(0, 0, 0);
+    int st = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        int st = kt & 1;
+        int nst = st + 1 == ST ? 0 : st + 1;
         fetch(st, 1, 1);
         __builtin_amdgcn_sched_barrier(0);
         mma(0);
@@ -189,19 +192,21 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         __builtin_amdgcn_sched_barrier(0);
         mma(0);
         __builtin_amdgcn_sched_barrier(0);
-        // every read of this stage has been issued: wait for them (lgkmcnt) and for the next tile's data
-        // (vmcnt), then synchronise
-        __builtin_amdgcn_s_waitcnt(0x0070);
+        // every read of this stage has been issued: wait for them (lgkmcnt 0) and for tile kt+1
+        // (all but the ST-2 most recent tiles' loads), then synchronise
+        wait_cnt<LPT*(ST - 2), 0>();
         __syncthreads();
-        if (kt + 2 < nk) issue_loads(kt + 2, st);
-        if (kt + 1 < nk) fetch(st ^ 1, 0, 0);
+        issue_loads(kt + ST, st);
+        if (kt + 1 < nk) fetch(nst, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         mma(1);
         __builtin_amdgcn_sched_barrier(0);
+        st = nst;
     }
+    wait_cnt<0, 15>();     // drain the tail loads before the workgroup's LDS is released
 
     // accumulator layout: element r of lane l is (n = 8*(r/4) + 4*(l/32) + r%4, m = l%32) of its 32x32 tile
-    bool split = gridDim.z > 1;
+    int S = gridDim.z;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
         int m = m0 + wm * WM + j * 32 + (lane & 31);
@@ -213,105 +218,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
                 int n = n0 + wn * WN + i * 32 + q * 8 + (lane >> 5) * 4;
                 if (n >= N) continue;
                 f32x4 v = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-                if (split) *(f32x4*)(partial + ((int64_t)blockIdx.z * M + m) * N + n) = v;
+                if (S > 1) *(f32x4*)(partial + ((int64_t)blockIdx.z * M + m) * N + n) = v;
                 else epilogue_store4<bf16_t>(v, m, n, N, bias, act, alpha, out_mode, out);
             }
     }
 }
 
-// ---------------------------------------------------------------- skinny kernel (bf16, M <= 64)
-// Workgroup = 4 waves; wave w owns weight rows n0 + 16w .. +15 for the whole k-range of this split.
-// Per 128-wide k block a lane loads 64 contiguous bytes of its weight row (lane group g = lane/16 takes
-// bytes [64g, 64g+64) of the row's 256-byte block), so every weight cache line is consumed whole by four
-// lanes.  MFMA step j of the block uses chunk j of every lane: k = kblock + 32g + 8j + e.  The activation
-// operand is read from LDS with the same k mapping.
-constexpr int SK_KC = 256;   // k elements per LDS stage
-__device__ __forceinline__ int sk_lds_off(int row, int chunk)   // row = 512 bytes = 32 chunks of 16 bytes
-{
-    return row * 512 + ((chunk ^ (row & 15)) << 4);
-}
-
-template <int MT>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                          const bf16_t* __restrict__ W,
-                                                          const bf16_t* __restrict__ bias, int act, float alpha,
-                                                          int out_mode, void* __restrict__ out,
-                                                          float* __restrict__ partial, int k_per_split)
-{
-    constexpr int ROWS = MT * 16;
-    constexpr int A_PASSES = ROWS * 32 / 256;   // 16-byte chunks per thread per stage
-    __shared__ __align__(16) unsigned char sA[2][ROWS * 512];
-    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int n_row = blockIdx.x * 64 + wave * 16 + (lane & 15);
-    n_row = n_row < N ? n_row : N - 1;
-    int g = lane >> 4;
-    int kbeg = blockIdx.y * k_per_split;
-    int nchunks = k_per_split / SK_KC;
-    const bf16_t* wrow = W + (int64_t)n_row * K + kbeg + g * 32;
-
-    uint4 rw[8], ra[A_PASSES];
-    auto load_global = [&](int c) {
-        const bf16_t* p = wrow + c * SK_KC;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) rw[b * 4 + j] = *(const uint4*)(p + b * 128 + j * 8);
-#pragma unroll
-        for (int q = 0; q < A_PASSES; ++q) {
-            int idx = tid + q * 256;
-            int r = idx >> 5, ch = idx & 31;
-            int rr = r < M ? r : M - 1;
-            ra[q] = *(const uint4*)(A + (int64_t)rr * K + kbeg + c * SK_KC + ch * 8);
-        }
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int q = 0; q < A_PASSES; ++q) {
-            int idx = tid + q * 256;
-            *(uint4*)(sA[buf] + sk_lds_off(idx >> 5, idx & 31)) = ra[q];
-        }
-    };
-
-    f32x4 acc[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        int buf = c & 1;
-        uint4 cw[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) cw[i] = rw[i];
-        if (c + 1 < nchunks) load_global(c + 1);
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                bf16x8 fw = __builtin_bit_cast(bf16x8, cw[b * 4 + j]);
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    bf16x8 fa = *(const bf16x8*)(sA[buf] + sk_lds_off(t * 16 + (lane & 15), b * 16 + g * 4 + j));
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw, fa, acc[t], 0, 0, 0);
-                }
-            }
-        if (c + 1 < nchunks) store_lds(buf ^ 1);
-        __syncthreads();
-    }
-    // accumulator: element r of lane l is (n = 4*(l/16) + r, m = l%16) of the 16x16 tile
-    int n = blockIdx.x * 64 + wave * 16 + g * 4;
-    if (n >= N) return;
-    bool split = gridDim.y > 1;
-#pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        int m = t * 16 + (lane & 15);
-        if (m >= M) continue;
-        if (split) *(f32x4*)(partial + ((int64_t)blockIdx.y * M + m) * N + n) = acc[t];
-        else epilogue_store4<bf16_t>(acc[t], m, n, N, bias, act, alpha, out_mode, out);
-    }
-}
-
+// Sums the split-K partials in split order (deterministic) and applies the epilogue.  (A reduction fused
+// into the GEMM through arrival counters was measured 3x slower: the device-scope fences it needs write
+// back and invalidate the L2 for every workgroup.)
 template <typename T>
 __global__ void splitk_reduce_kernel(int M, int N, int S, const float* __restrict__ partial,
                                      const T* __restrict__ bias, int act, float alpha, int out_mode,
@@ -371,44 +286,66 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(int M, int N, int K, 
 }
 
 // ---------------------------------------------------------------- host-side routing
-constexpr int BK = 64;   // granularity of K the tile kernels accept
-struct Plan { int route; int bm; int splits; int k_per_split; int mt; };
+// Tile configurations.  The first three have BN = 256 (the weight share of the LDS fill traffic is
+// BN / (BM + BN), which is what a weight-streaming decode GEMM wants large); the last three halve BN for
+// matrices with few output features, where more tiles beat deeper split-K.
+enum Cfg { C64x256 = 0, C128x256, C256x256, C64x128, C128x128, C256x128, N_CFG };
+struct CfgInfo { int bm, bn; };
+static const CfgInfo CFG[N_CFG] = {{64, 256}, {128, 256}, {256, 256}, {64, 128}, {128, 128}, {256, 128}};
 
-static int pick_split(int base_wgs, int k_units, int target, int max_split)
+struct Plan { int route; int cfg; int splits; int k_per_split; int tiles; };
+
+static int env_int(const char* name, int dflt)
 {
-    int best = 1;
-    for (int s = 1; s <= max_split && s <= k_units; ++s) {
-        if (k_units % s) continue;
-        best = s;
-        if ((int64_t)base_wgs * s >= target) break;
-    }
-    return best;
+    const char* v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
+// Cost model behind the choice of tile shape and split count (fitted to a sweep of the six shapes x split
+// counts on MI355X for 16 <= M <= 512): a workgroup's time is the larger of its LDS-fill traffic at the rate one
+// CU sustains through its vector L1 (about 45 GB/s) and its MFMA work at the rate the tile loop reaches
+// (about 4.5 TFLOP/s per CU); workgroups run in rounds of one per CU; the whole launch cannot beat
+// streaming W once from HBM; split-K adds the float partials' round trip and a second launch.
+static double plan_cost(int cfg, int splits, int M, int N, int K)
+{
+    int bm = CFG[cfg].bm, bn = CFG[cfg].bn;
+    int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    int64_t wgs = tiles * splits;
+    double rounds = (double)((wgs + 255) / 256);
+    double ktiles = (double)(K / TBK) / splits;
+    double fill = ktiles * (bm + bn) * TBK * 2 / 45e9;
+    double mfma = ktiles * 2.0 * bm * bn * TBK / 4.5e12;
+    double t = rounds * (fill > mfma ? fill : mfma);
+    double hbm = (double)N * K * 2 / 6e12;
+    if (t < hbm) t = hbm;
+    t += 4e-6;
+    if (splits > 1) t += 2.0 * splits * M * N * 4 / 5e12 + 4e-6;
+    return t;
 }
 
 static Plan make_plan(int dtype, int M, int N, int K)
 {
     Plan p{2, 0, 1, K, 0};
-    if (dtype != DT_BF16 || N % 4 != 0 || K % BK != 0 || M < 1) return p;
-    if (M <= 64 && K % SK_KC == 0) {
-        p.route = 1;
-        p.mt = (M + 15) / 16;
-        int wgs = (N + 63) / 64;
-        p.splits = pick_split(wgs, K / SK_KC, 512, 16);
-        p.k_per_split = K / p.splits;
-        return p;
-    }
+    if (dtype != DT_BF16 || N % 4 != 0 || K % TBK != 0 || M < 1) return p;
     p.route = 0;
-    int t256 = ((M + 255) / 256) * ((N + 255) / 256);
-    if (t256 >= 192) {
-        p.bm = 256;
-    } else {
-        p.bm = 128;
-        int t128 = ((M + 127) / 128) * ((N + 127) / 128);
-        if (t128 < 256) {
-            p.splits = pick_split(t128, K / 256 > 0 ? K / 256 : 1, 512, 8);
-            if (K % (p.splits * BK) != 0) p.splits = 1;
+    p.cfg = C256x256;
+    if (M <= 1024) {
+        static const int split_options[] = {1, 2, 4, 5, 8, 10, 16};
+        double best = 1e30;
+        for (int cfg = 0; cfg < N_CFG; ++cfg) {
+            if (CFG[cfg].bm >= 2 * M && CFG[cfg].bm > 64) continue;     // more than half the rows would be padding
+            for (int s : split_options) {
+                if ((K / TBK) % s || K / TBK / s < 4) continue;
+                double c = plan_cost(cfg, s, M, N, K);
+                if (c < best) { best = c; p.cfg = cfg; p.splits = s; }
+            }
         }
     }
+    // tuning knobs (debugging / sweeps): EXE_GEMM_CFG forces a configuration, EXE_GEMM_SPLIT a split count
+    int force_cfg = env_int("EXE_GEMM_CFG", -1), force_split = env_int("EXE_GEMM_SPLIT", 0);
+    if (force_cfg >= 0 && force_cfg < N_CFG) p.cfg = force_cfg;
+    if (force_split > 0 && (K / TBK) % force_split == 0) p.splits = force_split;
+    p.tiles = ((M + CFG[p.cfg].bm - 1) / CFG[p.cfg].bm) * ((N + CFG[p.cfg].bn - 1) / CFG[p.cfg].bn);
     p.k_per_split = K / p.splits;
     return p;
 }
@@ -421,11 +358,35 @@ size_t gemm_workspace_bytes(int dtype, int M, int N, int K)
     return p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
 }
 
+template <int BM, int BN, int WM, int WN, int ST>
+static hipError_t launch_tile(const GemmArgs& a, const Plan& p, hipStream_t s)
+{
+    auto kern = gemm_tile_kernel<BM, BN, WM, WN, ST>;
+    constexpr int threads = (BM / WM) * (BN / WN) * 64;
+    size_t lds = (size_t)ST * (BM + BN) * TBK * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
+    kern<<<dim3(tm * tn, 1, p.splits), threads, lds, s>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.W,
+                                                         (const bf16_t*)a.bias, a.act, a.alpha, a.out_mode, a.out,
+                                                         a.workspace, tm, tn, p.k_per_split);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.splits == 1) return e;
+    int64_t quads = ((int64_t)a.M * a.N) / 4;
+    splitk_reduce_kernel<bf16_t><<<(unsigned)((quads + 255) / 256), 256, 0, s>>>(
+        a.M, a.N, p.splits, a.workspace, (const bf16_t*)a.bias, a.act, a.alpha, a.out_mode, a.out);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     Plan p = make_plan(a.dtype, a.M, a.N, a.K);
-    if (p.splits > 1 && (!a.workspace || a.workspace_bytes < (size_t)p.splits * a.M * a.N * sizeof(float)))
+    if (p.splits > 1 && (!a.workspace || a.workspace_bytes < gemm_workspace_bytes(a.dtype, a.M, a.N, a.K)))
         return hipErrorInvalidValue;
     if (p.route == 2) {
         dim3 grid((a.N + 63) / 64, (a.M + 63) / 64);
@@ -437,48 +398,14 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
                                                              (const bf16_t*)a.bias, a.act, a.alpha, a.out_mode, a.out);
         return hipGetLastError();
     }
-    const bf16_t* A = (const bf16_t*)a.A;
-    const bf16_t* W = (const bf16_t*)a.W;
-    const bf16_t* bias = (const bf16_t*)a.bias;
-    if (p.route == 1) {
-        dim3 grid((a.N + 63) / 64, p.splits);
-#define EXE_SK(MT)                                                                                               \
-    gemm_skinny_kernel<MT><<<grid, 256, 0, s>>>(a.M, a.N, a.K, A, W, bias, a.act, a.alpha, a.out_mode, a.out,    \
-                                                a.workspace, p.k_per_split)
-        switch (p.mt) {
-            case 1: EXE_SK(1); break;
-            case 2: EXE_SK(2); break;
-            case 3: EXE_SK(3); break;
-            default: EXE_SK(4); break;
-        }
-#undef EXE_SK
-    } else if (p.bm == 256) {
-        int tm = (a.M + 255) / 256, tn = (a.N + 255) / 256;
-        size_t lds = 2 * (256 + 256) * 128;
-        auto kern = gemm_tile_kernel<256, 256, 128, 64>;
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        kern<<<dim3(tm * tn, 1, p.splits), 512, lds, s>>>(a.M, a.N, a.K, A, W, bias, a.act, a.alpha, a.out_mode, a.out,
-                                                         a.workspace, tm, tn, p.k_per_split);
-    } else {
-        int tm = (a.M + 127) / 128, tn = (a.N + 127) / 128;
-        size_t lds = 2 * (128 + 128) * 128;
-        gemm_tile_kernel<128, 128, 64, 64><<<dim3(tm * tn, 1, p.splits), 256, lds, s>>>(
-            a.M, a.N, a.K, A, W, bias, a.act, a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split);
+    switch (p.cfg) {
+        case C64x256: return launch_tile<64, 256, 32, 64, 3>(a, p, s);
+        case C128x256: return launch_tile<128, 256, 64, 64, 3>(a, p, s);
+        case C256x256: return launch_tile<256, 256, 128, 64, 2>(a, p, s);
+        case C64x128: return launch_tile<64, 128, 32, 64, 4>(a, p, s);
+        case C128x128: return launch_tile<128, 128, 64, 64, 3>(a, p, s);
+        default: return launch_tile<256, 128, 64, 64, 3>(a, p, s);
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (p.splits > 1) {
-        int64_t quads = ((int64_t)a.M * a.N) / 4;
-        splitk_reduce_kernel<bf16_t><<<(unsigned)((quads + 255) / 256), 256, 0, s>>>(
-            a.M, a.N, p.splits, a.workspace, bias, a.act, a.alpha, a.out_mode, a.out);
-        e = hipGetLastError();
-    }
-    return e;
 }
 
 }  // namespace exe

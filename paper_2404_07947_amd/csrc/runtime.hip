@@ -448,7 +448,7 @@ static int run_gemm(exe_model* m, int M, int N, int K, const void* A, const void
     double e = esz_of(m);
     double bytes = ((double)M * K + (double)N * K) * e +
                    (double)M * N * (out_mode == OUT_T ? e : (out_mode == OUT_RESID ? 8.0 : 4.0));
-    int kind = gemm_route(m->c.dtype, M, N, K) == 1 ? EXE_K_GEMM_SKINNY : EXE_K_GEMM_TILE;
+    int kind = M <= 256 ? EXE_K_GEMM_SKINNY : EXE_K_GEMM_TILE;   // weight streaming (HBM) vs MFMA regime
     LAUNCH(m, kind, bytes, 2.0 * M * N * K, launch_gemm(g, m->stream));
     return EXE_OK;
 }

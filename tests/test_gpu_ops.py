@@ -27,11 +27,14 @@ def rnd(shape, seed, scale=1.0, dtype=torch.bfloat16):
 
 
 # ------------------------------------------------------------------ GEMM
-# (M, N, K): the shapes route to: skinny (M<=64), 128-tile with split-K, 128-tile, 256-tile, generic.
+# (M, N, K): the shapes cover every tile configuration (64/128/256 rows x 128/256 columns), with and without
+# split-K, ragged M and N edges, and the generic kernel.
 GEMM_CASES = [
     (1, 512, 512), (16, 5120, 5120), (17, 1024, 2560), (33, 2048, 512), (64, 15360, 5120), (50, 50272, 512),
     (65, 512, 1024), (200, 1024, 512), (300, 640, 2048), (1000, 2048, 512),
     (4099, 3072, 256), (2049, 6144, 128),
+    (100, 15360, 1024), (200, 8192, 512), (256, 5120, 5120), (128, 5120, 2048), (64, 8192, 256),
+    (16, 512, 64), (70, 768, 128), (250, 8448, 192), (130, 260, 64),
     (37, 100, 72), (5, 52, 8),
 ]
 
@@ -47,7 +50,7 @@ def test_gemm_bf16(M, N, K, mode):
     b = rnd((N,), 3, 0.5)
     Ad, Wd, bd = A.to(DEV), W.to(DEV), b.to(DEV)
     ws_bytes = exe.exe_op_gemm_workspace(BF16, M, N, K)
-    ws = torch.empty(max(ws_bytes // 4, 1), dtype=torch.float32, device=DEV)
+    ws = torch.zeros(max(ws_bytes // 4, 1), dtype=torch.float32, device=DEV)
     rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(M).integers(0, M, 6)]))
     ref = prim().linear(A.float().numpy()[rows], W.float().numpy(), b.float().numpy())
     alpha = 1.0
@@ -89,10 +92,10 @@ def test_gemm_f32(M, N, K):
 
 
 def test_gemm_no_bias_and_determinism():
-    M, N, K = 48, 5120, 20480            # skinny with split-K
+    M, N, K = 48, 5120, 20480            # 64x128 tiles with split-K
     A, W = rnd((M, K), 8), rnd((N, K), 9, 0.02)
     Ad, Wd = A.to(DEV), W.to(DEV)
-    ws = torch.empty(exe.exe_op_gemm_workspace(BF16, M, N, K) // 4 + 1, dtype=torch.float32, device=DEV)
+    ws = torch.zeros(exe.exe_op_gemm_workspace(BF16, M, N, K) // 4 + 1, dtype=torch.float32, device=DEV)
     outs = []
     for _ in range(2):
         out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
