@@ -139,15 +139,22 @@ int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used_bytes, uin
 /*
  * Latency table for a scheduler (Section 3 "XProfiler": for a single layer, the attention kernel is
  * timed separately from the rest of the layer, over batch sizes and sequence lengths).
- *  phase 0: encode -- `batch` sequences of `length` input tokens (or lengths drawn from `dist`).
- *  phase 1: decode -- `batch` sequences whose K/V length is `length` (or drawn from `dist`).
- * One row per (batch, length) pair, batch-major.  Times are per layer, in milliseconds, averaged over
- * n_steps timed repetitions after 3 warm-up ones; K/V of a single layer is allocated from the model's pool,
- * which must hold no live sequence.  full_step_ms = n_layers*(attn+rest) + head_ms is an extrapolation.
+ *  phase 0: encode -- `batch` sequences of `length` input tokens.
+ *  phase 1: decode -- `batch` sequences whose self-attention K/V length (after the append) is `length`;
+ *           encoder-decoder models: cross-attention length is `length`, self-attention length max(1, length/12).
+ *  dist NULL or kind 0: every sequence has exactly `length`; kind 1: lengths ~ Normal(length, dist->std) rounded
+ *  and clipped to [dist->lo, dist->hi], drawn from dist->seed (the row's `ragged` is then 1).
+ * One row per (batch, length) pair, batch-major.  A single layer (layer 0's weights) runs n_steps timed
+ * repetitions after 3 warm-up ones; only that layer's K/V is allocated (from the model's pool, which must
+ * hold no live sequence; it is returned afterwards).  attn_ms_per_layer is the attention kernels' own time
+ * (HIP events around each launch); rest_ms_per_layer is the whole layer's latency (events around the layer,
+ * launch gaps included) minus it; std_ms is the standard deviation of the whole-layer latency; head_ms is the
+ * final norm + LM head + argmax (encoder-decoder encode: final norm + every decoder layer's cross K/V
+ * projection); full_step_ms = layers * (attn + rest) + head_ms is an extrapolation to the full depth.
  */
 typedef struct exe_profile_row {
     int32_t phase, batch, length, ragged;
-    int32_t total_tokens;          /* encode: sum of lengths; decode: sum of K/V lengths */
+    int32_t total_tokens;          /* sum of the row's lengths */
     float attn_ms_per_layer, rest_ms_per_layer, head_ms, full_step_ms, std_ms;
     int32_t n_timed;
 } exe_profile_row_t;

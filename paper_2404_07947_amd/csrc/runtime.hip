@@ -476,8 +476,8 @@ static float attn_scale(const exe_model* m)
     return m->c.scale_mode == EXE_SCALE_RSQRT_DH ? 1.f / sqrtf((float)m->c.head_dim) : 1.f;
 }
 
-// final norm of selected rows, LM head, argmax; copies tokens to host and logits to out_device
-static int run_head(exe_model* m, const int32_t* row_index_dev, int n, int32_t* next_tokens, void* out_device)
+// final norm of selected rows, LM head, argmax (launches only)
+static int head_launches(exe_model* m, const int32_t* row_index_dev, int n)
 {
     const exe_config_t& c = m->c;
     int r;
@@ -485,6 +485,15 @@ static int run_head(exe_model* m, const int32_t* row_index_dev, int n, int32_t* 
     if ((r = run_norm(m, row_index_dev, n, m->fin_g, m->fin_b, out_scale, m->a_last))) return r;
     if ((r = run_gemm(m, n, c.vocab, c.d_model, m->a_last, m->tok_emb, nullptr, -1, 1.f, OUT_F32, m->logits))) return r;
     LAUNCH(m, EXE_K_OTHER, (double)n * c.vocab * 4.0, 0.0, launch_argmax(m->logits, n, c.vocab, m->d_next, m->stream));
+    return EXE_OK;
+}
+
+// head, then tokens to the host and logits to out_device; synchronises the stream
+static int run_head(exe_model* m, const int32_t* row_index_dev, int n, int32_t* next_tokens, void* out_device)
+{
+    const exe_config_t& c = m->c;
+    int r = head_launches(m, row_index_dev, n);
+    if (r) return r;
     if (next_tokens) HIP_TRY(hipMemcpyAsync(m->h_next, m->d_next, (size_t)n * 4, hipMemcpyDeviceToHost, m->stream));
     if (out_device)
         HIP_TRY(hipMemcpyAsync(out_device, m->logits, (size_t)n * c.vocab * 4, hipMemcpyDeviceToDevice, m->stream));
@@ -510,30 +519,93 @@ struct EncodeDesc {
     int n_tiles;
 };
 
-static int encode_layers(exe_model* m, int n, int T, const EncodeDesc& d, const std::vector<int>& lens)
+// One encode (prefill) layer over T packed tokens of n sequences.  parts: bit 0 = everything but the
+// attention kernel, bit 1 = the attention kernel (the profiler times them separately).
+static int encode_layer(exe_model* m, const DecLayerW& L, int layer, int n, int T, const EncodeDesc& d,
+                        double attn_bytes, double attn_flops, int parts)
 {
     const exe_config_t& c = m->c;
     bool encdec = c.arch == EXE_ARCH_ENC_DEC;
-    std::vector<DecLayerW>& layers = encdec ? m->enc : m->dec;
-    double attn_flops = 0;
-    for (int L : lens) attn_flops += encdec ? 4.0 * m->inner * (double)L * L : 2.0 * m->inner * (double)L * (L + 1);
-    double attn_bytes = 4.0 * T * m->inner * esz_of(m);
     int r;
-    for (size_t l = 0; l < layers.size(); ++l) {
-        const DecLayerW& L = layers[l];
+    if (parts & 1) {
         if ((r = run_norm(m, nullptr, T, L.n1_g, L.n1_b, 1.f, m->a))) return r;
         if ((r = run_gemm(m, T, 3 * m->inner, c.d_model, m->a, L.w_qkv, L.b_qkv, -1, 1.f, OUT_T, m->qkv))) return r;
         if (!encdec)
             LAUNCH(m, EXE_K_OTHER, 4.0 * T * m->inner * esz_of(m), 0.0,
                    launch_kv_append(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, T, d.tok_b, d.tok_pos, d.base,
-                                    d.cap, (int)l, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
+                                    d.cap, layer, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
+    }
+    if (parts & 2) {
         AttnPackedArgs a{c.dtype, T, c.n_heads, c.head_dim, n, m->qkv, d.tok_b, d.tok_pos, d.cu, encdec ? 0 : 1,
                          attn_scale(m), encdec ? m->bias_enc : nullptr, m->radius, m->ctx, d.tiles, d.n_tiles, 0};
         LAUNCH(m, EXE_K_PREFILL_ATTN, attn_bytes, attn_flops, launch_attn_packed(a, m->stream));
+    }
+    if (parts & 1) {
         if ((r = run_gemm(m, T, c.d_model, m->inner, m->ctx, L.w_o, L.b_o, -1, 1.f, OUT_RESID, m->h))) return r;
         if ((r = run_ffn(m, T, L))) return r;
     }
     return EXE_OK;
+}
+
+static void prefill_attn_work(const exe_model* m, const std::vector<int>& lens, int T, double* bytes, double* flops)
+{
+    bool encdec = m->c.arch == EXE_ARCH_ENC_DEC;
+    double f = 0;
+    for (int L : lens) f += encdec ? 4.0 * m->inner * (double)L * L : 2.0 * m->inner * (double)L * (L + 1);
+    *flops = f;
+    *bytes = 4.0 * T * m->inner * esz_of(m);
+}
+
+static int encode_layers(exe_model* m, int n, int T, const EncodeDesc& d, const std::vector<int>& lens)
+{
+    std::vector<DecLayerW>& layers = m->c.arch == EXE_ARCH_ENC_DEC ? m->enc : m->dec;
+    double attn_bytes, attn_flops;
+    prefill_attn_work(m, lens, T, &attn_bytes, &attn_flops);
+    for (size_t l = 0; l < layers.size(); ++l) {
+        int r = encode_layer(m, layers[l], (int)l, n, T, d, attn_bytes, attn_flops, 3);
+        if (r) return r;
+    }
+    return EXE_OK;
+}
+
+// fills the per-token and per-sequence descriptor arrays of an encode batch (host side) and the tile list
+static void fill_encode_desc(exe_model* m, Stager& st, EncodeDesc& d, int n, const std::vector<int>& lens,
+                             const int32_t* tokens, const std::vector<Seq>& fresh)
+{
+    bool encdec = m->c.arch == EXE_ARCH_ENC_DEC;
+    int T = 0;
+    for (int L : lens) T += L;
+    int32_t* h_tok = st.take<int32_t>(T, &d.tok);
+    int32_t* h_tb = st.take<int32_t>(T, &d.tok_b);
+    int32_t* h_tp = st.take<int32_t>(T, &d.tok_pos);
+    int32_t* h_cu = st.take<int32_t>(n + 1, &d.cu);
+    int32_t* h_cap = st.take<int32_t>(n, &d.cap);
+    int32_t* h_last = st.take<int32_t>(n, &d.last);
+    int32_t* h_xcap = st.take<int32_t>(n, &d.xcap);
+    int64_t* h_base = st.take<int64_t>(n, &d.base);
+    int64_t* h_xbase = st.take<int64_t>(n, &d.xbase);
+    std::vector<std::pair<int, std::pair<int, int>>> tl;   // (work, (seq, q0))
+    int t = 0;
+    for (int i = 0; i < n; ++i) {
+        h_cu[i] = t;
+        for (int p = 0; p < lens[i]; ++p, ++t) {
+            h_tok[t] = tokens ? tokens[t] : 0;
+            h_tb[t] = i;
+            h_tp[t] = p;
+        }
+        h_cap[i] = encdec ? 0 : fresh[i].cap;
+        h_base[i] = encdec ? 0 : fresh[i].base;
+        h_xcap[i] = encdec ? round8(lens[i]) : 0;
+        h_xbase[i] = encdec ? fresh[i].xbase : 0;
+        h_last[i] = t - 1;
+        for (int q0 = 0; q0 < lens[i]; q0 += PREFILL_TILE_Q)
+            tl.push_back({encdec ? lens[i] : std::min(lens[i], q0 + PREFILL_TILE_Q), {i, q0}});
+    }
+    h_cu[n] = t;
+    std::stable_sort(tl.begin(), tl.end(), [](const auto& x, const auto& y) { return x.first > y.first; });
+    int32_t* h_tiles = st.take<int32_t>(2 * tl.size(), &d.tiles);
+    d.n_tiles = (int)tl.size();
+    for (size_t k = 0; k < tl.size(); ++k) { h_tiles[2 * k] = tl[k].second.first; h_tiles[2 * k + 1] = tl[k].second.second; }
 }
 
 extern "C" int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, const int32_t* input_lengths,
@@ -605,37 +677,7 @@ extern "C" int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, con
     // descriptors
     Stager st{m};
     EncodeDesc d{};
-    int32_t* h_tok = st.take<int32_t>(T, &d.tok);
-    int32_t* h_tb = st.take<int32_t>(T, &d.tok_b);
-    int32_t* h_tp = st.take<int32_t>(T, &d.tok_pos);
-    int32_t* h_cu = st.take<int32_t>(n + 1, &d.cu);
-    int32_t* h_cap = st.take<int32_t>(n, &d.cap);
-    int32_t* h_last = st.take<int32_t>(n, &d.last);
-    int32_t* h_xcap = st.take<int32_t>(n, &d.xcap);
-    int64_t* h_base = st.take<int64_t>(n, &d.base);
-    int64_t* h_xbase = st.take<int64_t>(n, &d.xbase);
-    std::vector<std::pair<int, std::pair<int, int>>> tl;   // (work, (seq, q0))
-    int t = 0;
-    for (int i = 0; i < n; ++i) {
-        h_cu[i] = t;
-        for (int p = 0; p < lens[i]; ++p, ++t) {
-            h_tok[t] = c.has_embed ? tokens_packed[t] : 0;
-            h_tb[t] = i;
-            h_tp[t] = p;
-        }
-        h_cap[i] = encdec ? 0 : fresh[i].cap;
-        h_base[i] = encdec ? 0 : fresh[i].base;
-        h_xcap[i] = encdec ? round8(lens[i]) : 0;
-        h_xbase[i] = encdec ? fresh[i].xbase : 0;
-        h_last[i] = t - 1;
-        for (int q0 = 0; q0 < lens[i]; q0 += PREFILL_TILE_Q)
-            tl.push_back({encdec ? lens[i] : std::min(lens[i], q0 + PREFILL_TILE_Q), {i, q0}});
-    }
-    h_cu[n] = t;
-    std::stable_sort(tl.begin(), tl.end(), [](const auto& x, const auto& y) { return x.first > y.first; });
-    int32_t* h_tiles = st.take<int32_t>(2 * tl.size(), &d.tiles);
-    d.n_tiles = (int)tl.size();
-    for (size_t k = 0; k < tl.size(); ++k) { h_tiles[2 * k] = tl[k].second.first; h_tiles[2 * k + 1] = tl[k].second.second; }
+    fill_encode_desc(m, st, d, n, lens, c.has_embed ? tokens_packed : nullptr, fresh);
     if (st.off > m->stage_bytes) { rollback(); return fail(EXE_ERR_ARG, "descriptor staging overflow"); }
 
     auto body = [&]() -> int {
@@ -682,6 +724,97 @@ extern "C" int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, con
 }
 
 // ---------------------------------------------------------------- decode step
+struct DecodeSeq { int32_t token; int len_before; int cap; int64_t base; int n_in; int64_t xbase; };
+struct DecodeDesc {
+    int32_t *tok, *pos, *len, *cap, *xcap, *xlen;
+    int64_t *base, *xbase;
+    double self_bytes, self_flops, x_bytes, x_flops;
+};
+
+static void fill_decode_desc(exe_model* m, Stager& st, DecodeDesc& d, const std::vector<DecodeSeq>& ds)
+{
+    int n = (int)ds.size();
+    int32_t* h_tok = st.take<int32_t>(n, &d.tok);
+    int32_t* h_pos = st.take<int32_t>(n, &d.pos);
+    int32_t* h_len = st.take<int32_t>(n, &d.len);
+    int32_t* h_cap = st.take<int32_t>(n, &d.cap);
+    int32_t* h_xcap = st.take<int32_t>(n, &d.xcap);
+    int32_t* h_xlen = st.take<int32_t>(n, &d.xlen);
+    int64_t* h_base = st.take<int64_t>(n, &d.base);
+    int64_t* h_xbase = st.take<int64_t>(n, &d.xbase);
+    double sum_len = 0, sum_x = 0;
+    for (int i = 0; i < n; ++i) {
+        h_tok[i] = ds[i].token;
+        h_pos[i] = ds[i].len_before;
+        h_len[i] = ds[i].len_before + 1;
+        h_cap[i] = ds[i].cap;
+        h_base[i] = ds[i].base;
+        h_xcap[i] = round8(ds[i].n_in);
+        h_xlen[i] = ds[i].n_in;
+        h_xbase[i] = ds[i].xbase;
+        sum_len += ds[i].len_before + 1;
+        sum_x += ds[i].n_in;
+    }
+    double e = esz_of(m);
+    d.self_bytes = (2.0 * sum_len + 2.0 * n) * m->inner * e;
+    d.self_flops = 4.0 * sum_len * m->inner;
+    d.x_bytes = (2.0 * sum_x + 2.0 * n) * m->inner * e;
+    d.x_flops = 4.0 * sum_x * m->inner;
+}
+
+// residual stream of the step's n rows from the token (+position) embedding, or from caller hidden states
+static int decode_input(exe_model* m, const DecodeDesc& d, int n, const void* hidden_in)
+{
+    const exe_config_t& c = m->c;
+    if (c.has_embed)
+        LAUNCH(m, EXE_K_OTHER, (double)n * c.d_model * (esz_of(m) + 4.0), 0.0,
+               launch_embed(c.dtype, d.tok, d.pos, n, c.d_model, m->tok_emb, m->pos_emb, m->h, m->stream));
+    else
+        LAUNCH(m, EXE_K_OTHER, (double)n * c.d_model * (esz_of(m) + 4.0), 0.0,
+               launch_load_hidden(c.dtype, hidden_in, (int64_t)n * c.d_model, m->h, m->stream));
+    return EXE_OK;
+}
+
+// One decode layer for n rows.  parts: bit 0 = everything but the attention kernels, bit 1 = the attention
+// kernels (self, and cross for encoder-decoder models).
+static int decode_layer(exe_model* m, const DecLayerW& L, int layer, int n, const DecodeDesc& d, int parts)
+{
+    const exe_config_t& c = m->c;
+    bool encdec = c.arch == EXE_ARCH_ENC_DEC;
+    double e = esz_of(m);
+    int r;
+    if (parts & 1) {
+        if ((r = run_norm(m, nullptr, n, L.n1_g, L.n1_b, 1.f, m->a))) return r;
+        if ((r = run_gemm(m, n, 3 * m->inner, c.d_model, m->a, L.w_qkv, L.b_qkv, -1, 1.f, OUT_T, m->qkv))) return r;
+        LAUNCH(m, EXE_K_OTHER, 4.0 * n * m->inner * e, 0.0,
+               launch_kv_append(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, n, nullptr, d.pos, d.base, d.cap,
+                                layer, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
+    }
+    if (parts & 2) {
+        AttnCacheArgs a{c.dtype, n, c.n_heads, c.head_dim, m->qkv, 3 * m->inner, m->pool.ptr, d.base, d.cap, d.len, d.pos,
+                        layer, attn_scale(m), encdec ? m->bias_dec : nullptr, m->radius, m->ctx};
+        LAUNCH(m, EXE_K_DECODE_ATTN, d.self_bytes, d.self_flops, launch_attn_cache(a, m->stream));
+    }
+    if (parts & 1)
+        if ((r = run_gemm(m, n, c.d_model, m->inner, m->ctx, L.w_o, L.b_o, -1, 1.f, OUT_RESID, m->h))) return r;
+    if (encdec) {
+        if (parts & 1) {
+            if ((r = run_norm(m, nullptr, n, L.nx_g, nullptr, 1.f, m->a))) return r;
+            if ((r = run_gemm(m, n, m->inner, c.d_model, m->a, L.w_xq, nullptr, -1, 1.f, OUT_T, m->qkv))) return r;
+        }
+        if (parts & 2) {
+            AttnCacheArgs x{c.dtype, n, c.n_heads, c.head_dim, m->qkv, m->inner, m->pool.ptr, d.xbase, d.xcap, d.xlen, d.pos,
+                            layer, attn_scale(m), m->bias_x, m->radius, m->ctx};
+            LAUNCH(m, EXE_K_CROSS_ATTN, d.x_bytes, d.x_flops, launch_attn_cache(x, m->stream));
+        }
+        if (parts & 1)
+            if ((r = run_gemm(m, n, c.d_model, m->inner, m->ctx, L.w_xo, nullptr, -1, 1.f, OUT_RESID, m->h))) return r;
+    }
+    if (parts & 1)
+        if ((r = run_ffn(m, n, L))) return r;
+    return EXE_OK;
+}
+
 extern "C" int exe_decode_step(exe_model_t* m, int32_t n, const int32_t* seq_ids, const int32_t* tokens_in,
                                const int32_t* kv_lengths, const void* hidden_in, int32_t* next_tokens, void* out_device)
 {
@@ -690,10 +823,8 @@ extern "C" int exe_decode_step(exe_model_t* m, int32_t n, const int32_t* seq_ids
     if (n < 1 || !seq_ids || !kv_lengths) return fail(EXE_ERR_ARG, "n < 1 or null seq_ids/kv_lengths");
     if (n > c.max_batch_seqs) return fail(EXE_ERR_ARG, "n = %d exceeds max_batch_seqs = %d", n, c.max_batch_seqs);
     if (c.has_embed ? !tokens_in : !hidden_in) return fail(EXE_ERR_ARG, "missing tokens_in / hidden_in");
-    bool encdec = c.arch == EXE_ARCH_ENC_DEC;
     bool learned = c.has_embed && c.pos == EXE_POS_LEARNED;
     ++m->mark_gen;
-    double sum_len = 0, sum_x = 0;
     for (int i = 0; i < n; ++i) {
         int id = seq_ids[i];
         if (id < 0 || id >= c.max_seqs || !m->seqs[id].live) return fail(EXE_ERR_BAD_SEQ, "seq id %d is not live", id);
@@ -704,63 +835,21 @@ extern "C" int exe_decode_step(exe_model_t* m, int32_t n, const int32_t* seq_ids
         if (s.len + 1 > s.cap) return fail(EXE_ERR_OOM_KV, "seq %d: reserved capacity %d exhausted", id, s.cap);
         if (learned && s.len + 1 > c.max_pos) return fail(EXE_ERR_BAD_LENGTH, "seq %d: position %d exceeds max_pos", id, s.len);
         if (c.has_embed && (tokens_in[i] < 0 || tokens_in[i] >= c.vocab)) return fail(EXE_ERR_ARG, "token %d out of range", tokens_in[i]);
-        sum_len += s.len + 1;
-        sum_x += s.n_in;
     }
     Stager st{m};
-    int32_t *d_tok, *d_pos, *d_len, *d_cap, *d_xcap, *d_xlen;
-    int64_t *d_base, *d_xbase;
-    int32_t* h_tok = st.take<int32_t>(n, &d_tok);
-    int32_t* h_pos = st.take<int32_t>(n, &d_pos);
-    int32_t* h_len = st.take<int32_t>(n, &d_len);
-    int32_t* h_cap = st.take<int32_t>(n, &d_cap);
-    int32_t* h_xcap = st.take<int32_t>(n, &d_xcap);
-    int32_t* h_xlen = st.take<int32_t>(n, &d_xlen);
-    int64_t* h_base = st.take<int64_t>(n, &d_base);
-    int64_t* h_xbase = st.take<int64_t>(n, &d_xbase);
+    DecodeDesc dd{};
+    std::vector<DecodeSeq> ds(n);
     for (int i = 0; i < n; ++i) {
         const Seq& s = m->seqs[seq_ids[i]];
-        h_tok[i] = c.has_embed ? tokens_in[i] : 0;
-        h_pos[i] = s.len;
-        h_len[i] = s.len + 1;
-        h_cap[i] = s.cap;
-        h_base[i] = s.base;
-        h_xcap[i] = round8(s.n_in);
-        h_xlen[i] = s.n_in;
-        h_xbase[i] = s.xbase < 0 ? 0 : s.xbase;
+        ds[i] = DecodeSeq{c.has_embed ? tokens_in[i] : 0, s.len, s.cap, s.base, s.n_in, s.xbase < 0 ? 0 : s.xbase};
     }
+    fill_decode_desc(m, st, dd, ds);
     HIP_TRY(hipMemcpyAsync(m->stage_d, m->stage_h, st.off, hipMemcpyHostToDevice, m->stream));
-    if (c.has_embed)
-        LAUNCH(m, EXE_K_OTHER, (double)n * c.d_model * (esz_of(m) + 4.0), 0.0,
-               launch_embed(c.dtype, d_tok, d_pos, n, c.d_model, m->tok_emb, m->pos_emb, m->h, m->stream));
-    else
-        LAUNCH(m, EXE_K_OTHER, (double)n * c.d_model * (esz_of(m) + 4.0), 0.0,
-               launch_load_hidden(c.dtype, hidden_in, (int64_t)n * c.d_model, m->h, m->stream));
     int r;
+    if ((r = decode_input(m, dd, n, hidden_in))) return r;
+    for (size_t l = 0; l < m->dec.size(); ++l)
+        if ((r = decode_layer(m, m->dec[l], (int)l, n, dd, 3))) return r;
     double e = esz_of(m);
-    double self_bytes = (2.0 * sum_len + 2.0 * n) * m->inner * e, self_flops = 4.0 * sum_len * m->inner;
-    double x_bytes = (2.0 * sum_x + 2.0 * n) * m->inner * e, x_flops = 4.0 * sum_x * m->inner;
-    for (size_t l = 0; l < m->dec.size(); ++l) {
-        const DecLayerW& L = m->dec[l];
-        if ((r = run_norm(m, nullptr, n, L.n1_g, L.n1_b, 1.f, m->a))) return r;
-        if ((r = run_gemm(m, n, 3 * m->inner, c.d_model, m->a, L.w_qkv, L.b_qkv, -1, 1.f, OUT_T, m->qkv))) return r;
-        LAUNCH(m, EXE_K_OTHER, 4.0 * n * m->inner * e, 0.0,
-               launch_kv_append(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, n, nullptr, d_pos, d_base, d_cap,
-                                (int)l, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
-        AttnCacheArgs a{c.dtype, n, c.n_heads, c.head_dim, m->qkv, 3 * m->inner, m->pool.ptr, d_base, d_cap, d_len, d_pos,
-                        (int)l, attn_scale(m), encdec ? m->bias_dec : nullptr, m->radius, m->ctx};
-        LAUNCH(m, EXE_K_DECODE_ATTN, self_bytes, self_flops, launch_attn_cache(a, m->stream));
-        if ((r = run_gemm(m, n, c.d_model, m->inner, m->ctx, L.w_o, L.b_o, -1, 1.f, OUT_RESID, m->h))) return r;
-        if (encdec) {
-            if ((r = run_norm(m, nullptr, n, L.nx_g, nullptr, 1.f, m->a))) return r;
-            if ((r = run_gemm(m, n, m->inner, c.d_model, m->a, L.w_xq, nullptr, -1, 1.f, OUT_T, m->qkv))) return r;
-            AttnCacheArgs x{c.dtype, n, c.n_heads, c.head_dim, m->qkv, m->inner, m->pool.ptr, d_xbase, d_xcap, d_xlen, d_pos,
-                            (int)l, attn_scale(m), m->bias_x, m->radius, m->ctx};
-            LAUNCH(m, EXE_K_CROSS_ATTN, x_bytes, x_flops, launch_attn_cache(x, m->stream));
-            if ((r = run_gemm(m, n, c.d_model, m->inner, m->ctx, L.w_xo, nullptr, -1, 1.f, OUT_RESID, m->h))) return r;
-        }
-        if ((r = run_ffn(m, n, L))) return r;
-    }
     if (c.has_lm_head) {
         if ((r = run_head(m, nullptr, n, next_tokens, out_device))) return r;
     } else {
@@ -807,13 +896,209 @@ extern "C" int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used
     return EXE_OK;
 }
 
+// ---------------------------------------------------------------- profile sweep
+// splitmix64 + Box-Muller: the same lengths on every platform
+struct Rng {
+    uint64_t s;
+    uint64_t next() { uint64_t z = (s += 0x9E3779B97F4A7C15ull); z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull; z = (z ^ (z >> 27)) * 0x94D049BB133111EBull; return z ^ (z >> 31); }
+    double uniform() { return ((next() >> 11) + 0.5) * (1.0 / 9007199254740992.0); }
+    double normal() { return std::sqrt(-2.0 * std::log(uniform())) * std::cos(6.283185307179586 * uniform()); }
+};
+
+struct EventTimer {
+    hipEvent_t a = nullptr, b = nullptr;
+    ~EventTimer() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
+    hipError_t init() { hipError_t e = hipEventCreate(&a); return e != hipSuccess ? e : hipEventCreate(&b); }
+};
+
+static double attn_ms_of(exe_model* m)
+{
+    exe_kernel_time_t rows[EXE_K_COUNT];
+    if (exe_kernel_times(m, rows)) return 0.0;
+    return rows[EXE_K_PREFILL_ATTN].ms + rows[EXE_K_DECODE_ATTN].ms + rows[EXE_K_CROSS_ATTN].ms;
+}
+
+// One row of the table: a single layer (layer 0's weights) on `lens`, K/V of one layer only.
+static int profile_row(exe_model* m, int phase, const std::vector<int>& lens, int n_steps, exe_profile_row_t* row)
+{
+    const exe_config_t& c = m->c;
+    bool encdec = c.arch == EXE_ARCH_ENC_DEC;
+    int n = (int)lens.size();
+    int64_t total = 0;
+    for (int L : lens) total += L;
+    row->total_tokens = (int32_t)std::min<int64_t>(total, 0x7fffffff);
+    if (n > c.max_batch_seqs) return fail(EXE_ERR_ARG, "profile batch %d exceeds max_batch_seqs %d", n, c.max_batch_seqs);
+    if (phase == 0 && total > c.max_batch_tokens) return fail(EXE_ERR_ARG, "profile batch of %lld tokens exceeds max_batch_tokens %d", (long long)total, c.max_batch_tokens);
+
+    // single-layer extents
+    std::vector<Seq> fresh(n);
+    auto rollback = [&]() {
+        for (auto& s : fresh) {
+            if (s.base >= 0) m->pool.release(s.base, s.elems);
+            if (s.xbase >= 0) m->pool.release(s.xbase, s.xelems);
+        }
+    };
+    for (int i = 0; i < n; ++i) {
+        Seq& s = fresh[i];
+        int self_len = encdec ? (phase == 0 ? 1 : std::max(1, lens[i] / 12)) : lens[i];
+        s.len = self_len;
+        s.cap = round8(self_len + 1);
+        s.elems = (int64_t)2 * m->inner * s.cap;
+        s.base = m->pool.alloc(s.elems);
+        bool ok = s.base >= 0;
+        if (ok && encdec) {
+            s.n_in = lens[i];
+            s.xelems = (int64_t)2 * m->inner * round8(lens[i]);
+            s.xbase = m->pool.alloc(s.xelems);
+            ok = s.xbase >= 0;
+        }
+        if (!ok) { rollback(); return fail(EXE_ERR_OOM_KV, "K/V pool too small for one layer of this profile row"); }
+    }
+    // K/V that is read without having been written by this run must be finite: 0x3c3c is 0.0115 in bf16,
+    // 0x3c3c3c3c is 0.0115 in float
+    hipError_t he = hipSuccess;
+    for (int i = 0; i < n && he == hipSuccess; ++i) {
+        he = hipMemsetAsync((char*)m->pool.ptr + fresh[i].base * m->esz, 0x3c, (size_t)fresh[i].elems * m->esz, m->stream);
+        if (he == hipSuccess && encdec)
+            he = hipMemsetAsync((char*)m->pool.ptr + fresh[i].xbase * m->esz, 0x3c, (size_t)fresh[i].xelems * m->esz, m->stream);
+    }
+    if (he == hipSuccess) he = hipMemsetAsync(m->h, 0, (size_t)m->rows_cap * c.d_model * sizeof(float), m->stream);
+    if (he != hipSuccess) { rollback(); return fail(EXE_ERR_HIP, "profile memset: %s", hipGetErrorString(he)); }
+
+    Stager st{m};
+    EncodeDesc ed{};
+    DecodeDesc dd{};
+    int rows_n;
+    const DecLayerW* L;
+    double ab = 0, af = 0;
+    if (phase == 0) {
+        fill_encode_desc(m, st, ed, n, lens, nullptr, fresh);
+        prefill_attn_work(m, lens, (int)total, &ab, &af);
+        rows_n = (int)total;
+        L = encdec ? &m->enc[0] : &m->dec[0];
+    } else {
+        std::vector<DecodeSeq> ds(n);
+        for (int i = 0; i < n; ++i)
+            ds[i] = DecodeSeq{0, fresh[i].len - 1 > 0 ? fresh[i].len - 1 : 0, fresh[i].cap, fresh[i].base, fresh[i].n_in,
+                              fresh[i].xbase < 0 ? 0 : fresh[i].xbase};
+        fill_decode_desc(m, st, dd, ds);
+        rows_n = n;
+        L = &m->dec[0];
+    }
+    auto layer = [&](int parts) -> int {
+        return phase == 0 ? encode_layer(m, *L, 0, n, rows_n, ed, ab, af, parts) : decode_layer(m, *L, 0, n, dd, parts);
+    };
+    auto body = [&]() -> int {
+        if (st.off > m->stage_bytes) return fail(EXE_ERR_ARG, "descriptor staging overflow");
+        HIP_TRY(hipMemcpyAsync(m->stage_d, m->stage_h, st.off, hipMemcpyHostToDevice, m->stream));
+        EventTimer t;
+        HIP_TRY(t.init());
+        int r;
+        for (int w = 0; w < 3; ++w)
+            if ((r = layer(3))) return r;
+        // pass A: whole-layer latency per repetition (launch gaps included), no per-kernel events
+        std::vector<double> layer_ms(n_steps);
+        for (int i = 0; i < n_steps; ++i) {
+            HIP_TRY(hipEventRecord(t.a, m->stream));
+            if ((r = layer(3))) return r;
+            HIP_TRY(hipEventRecord(t.b, m->stream));
+            HIP_TRY(hipEventSynchronize(t.b));
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, t.a, t.b));
+            layer_ms[i] = ms;
+        }
+        // pass B: the attention kernels alone, from events around each launch
+        bool was_on = m->timer.on;
+        exe_kernel_timing(m, 1);
+        double attn = 0;
+        for (int i = 0; i < n_steps; ++i) {
+            if ((r = layer(2))) { exe_kernel_timing(m, was_on); return r; }
+            attn += attn_ms_of(m);
+        }
+        exe_kernel_timing(m, was_on);
+        attn /= n_steps;
+        double mean = 0, var = 0;
+        for (double x : layer_ms) mean += x;
+        mean /= n_steps;
+        for (double x : layer_ms) var += (x - mean) * (x - mean);
+        row->attn_ms_per_layer = (float)attn;
+        row->rest_ms_per_layer = (float)std::max(0.0, mean - attn);
+        row->std_ms = (float)std::sqrt(var / n_steps);
+        // head: final norm + LM head + argmax (decode: n rows; encode: the last row of each sequence);
+        // encoder-decoder encode: final norm + one decoder layer's cross K/V projection and store
+        double head = 0;
+        if (phase == 0 && encdec) {
+            HIP_TRY(hipEventRecord(t.a, m->stream));
+            for (int i = 0; i < n_steps; ++i) {
+                if ((r = run_norm(m, nullptr, rows_n, m->enc_fin_g, nullptr, 1.f, m->a))) return r;
+                if ((r = run_gemm(m, rows_n, 2 * m->inner, c.d_model, m->a, m->dec[0].w_xkv, nullptr, -1, 1.f, OUT_T, m->qkv))) return r;
+                LAUNCH(m, EXE_K_OTHER, 0.0, 0.0,
+                       launch_kv_append(c.dtype, m->qkv, 2 * m->inner, 0, m->inner, rows_n, ed.tok_b, ed.tok_pos, ed.xbase,
+                                        ed.xcap, 0, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
+            }
+            HIP_TRY(hipEventRecord(t.b, m->stream));
+            HIP_TRY(hipEventSynchronize(t.b));
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, t.a, t.b));
+            head = ms / n_steps * c.n_dec_layers;
+        } else if (c.has_lm_head) {
+            HIP_TRY(hipEventRecord(t.a, m->stream));
+            for (int i = 0; i < n_steps; ++i)
+                if ((r = head_launches(m, phase == 0 ? ed.last : nullptr, n))) return r;
+            HIP_TRY(hipEventRecord(t.b, m->stream));
+            HIP_TRY(hipEventSynchronize(t.b));
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, t.a, t.b));
+            head = ms / n_steps;
+        }
+        row->head_ms = (float)head;
+        int layers = phase == 0 ? c.n_layers : n_dec_layers(c);
+        row->full_step_ms = (float)(layers * mean + head);
+        row->n_timed = n_steps;
+        return EXE_OK;
+    };
+    int r = body();
+    (void)hipStreamSynchronize(m->stream);
+    rollback();
+    return r;
+}
+
 extern "C" int exe_profile(exe_model_t* m, int32_t phase, const int32_t* batch_sizes, int32_t n_batch,
                            const int32_t* lengths, int32_t n_len, const exe_length_dist_t* dist, int32_t n_steps,
                            exe_profile_row_t* rows, int32_t rows_cap, int32_t* n_rows)
 {
-    (void)m; (void)phase; (void)batch_sizes; (void)n_batch; (void)lengths; (void)n_len; (void)dist; (void)n_steps;
-    (void)rows; (void)rows_cap; (void)n_rows;
-    return fail(EXE_ERR_UNIMPLEMENTED, "exe_profile is not implemented yet");
+    if (!m) return fail(EXE_ERR_ARG, "null model");
+    if (n_rows) *n_rows = 0;
+    if ((phase != 0 && phase != 1) || !batch_sizes || !lengths || n_batch < 1 || n_len < 1 || n_steps < 1 || !rows || !n_rows)
+        return fail(EXE_ERR_ARG, "bad profile arguments");
+    if (rows_cap < n_batch * n_len) return fail(EXE_ERR_ARG, "rows_cap %d < %d rows", rows_cap, n_batch * n_len);
+    if (m->live > 0) return fail(EXE_ERR_BAD_SEQ, "exe_profile needs a model with no live sequence (%d live)", m->live);
+    if (dist && dist->kind != 0 && dist->kind != 1) return fail(EXE_ERR_ARG, "bad length distribution kind");
+    bool ragged = dist && dist->kind == 1;
+    bool learned = m->c.has_embed && m->c.pos == EXE_POS_LEARNED;
+    for (int bi = 0; bi < n_batch; ++bi)
+        for (int li = 0; li < n_len; ++li) {
+            int B = batch_sizes[bi], Lm = lengths[li];
+            if (B < 1 || Lm < 1) return fail(EXE_ERR_ARG, "batch and length must be positive");
+            std::vector<int> lens(B, Lm);
+            if (ragged) {
+                Rng rng{dist->seed + (uint64_t)bi * 1000003ull + (uint64_t)li};
+                for (int i = 0; i < B; ++i) {
+                    double x = std::nearbyint((double)Lm + (double)dist->std * rng.normal());
+                    lens[i] = (int)std::min<double>(std::max<double>(x, dist->lo), dist->hi);
+                    if (lens[i] < 1) lens[i] = 1;
+                }
+            }
+            if (learned)
+                for (int& L : lens) L = std::min(L, m->c.max_pos - 1);
+            exe_profile_row_t* row = &rows[*n_rows];
+            memset(row, 0, sizeof(*row));
+            row->phase = phase; row->batch = B; row->length = Lm; row->ragged = ragged ? 1 : 0;
+            int r = profile_row(m, phase, lens, n_steps, row);
+            if (r) return r;
+            ++*n_rows;
+        }
+    return EXE_OK;
 }
 
 // ---------------------------------------------------------------- single-operation entry points
