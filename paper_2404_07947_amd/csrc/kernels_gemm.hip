@@ -163,13 +163,28 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 #pragma unroll
         for (int i = 0; i < TN; ++i) fw[b][i] = *(const bf16x8*)(sw + lds_off(wn * WN + i * 32 + frow, ks * 2 + fk));
     };
-    auto mma = [&](int b) {
+    // the MFMAs of one k-step in two halves, so that the next step's fragment fetch can be issued between them
+    auto mma = [&](int b, int half) {
+        constexpr int NM = TN * TM;
 #pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[b][i], fa[b][j], acc[i][j], 0, 0, 0);
+        for (int x = 0; x < NM; ++x) {
+            if ((x < NM / 2) != (half == 0) && NM > 1) continue;
+            if (NM == 1 && half == 1) continue;
+            int i = x / TM, j = x % TM;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[b][i], fa[b][j], acc[i][j], 0, 0, 0);
+        }
     };
+    // one k-step: first half of the MFMAs, then the fetch of the following step, then the second half.  The
+    // fragments a step needs were requested half a step earlier, so the wait in front of its MFMAs covers
+    // only loads that have had time to return.
+#define EXE_STEP(b, fetch_stmt)                  \
+    __builtin_amdgcn_sched_barrier(0);           \
+    mma(b, 0);                                   \
+    __builtin_amdgcn_sched_barrier(0);           \
+    fetch_stmt;                                  \
+    __builtin_amdgcn_sched_barrier(0);           \
+    mma(b, 1);                                   \
+    __builtin_amdgcn_sched_barrier(0);
 
     // prologue: tiles 0 .. ST-1 go to stages 0 .. ST-1; wait for tile 0 only
 #pragma unroll
@@ -180,29 +195,25 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int st = 0;
     for (int kt = 0; kt < nk; ++kt) {
         int nst = st + 1 == ST ? 0 : st + 1;
-        fetch(st, 1, 1);
+        EXE_STEP(0, fetch(st, 1, 1))
+        EXE_STEP(1, fetch(st, 2, 0))
+        EXE_STEP(0, fetch(st, 3, 1))
+        // last step of the tile.  After its first half every read of this stage has been issued and has
+        // returned (lgkmcnt 0); wait for tile kt+1 as well (all but the ST-2 most recent tiles' loads),
+        // synchronise, refill the stage just vacated and fetch the first fragments of tile kt+1.
         __builtin_amdgcn_sched_barrier(0);
-        mma(0);
+        mma(1, 0);
         __builtin_amdgcn_sched_barrier(0);
-        fetch(st, 2, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(1);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(st, 3, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(0);
-        __builtin_amdgcn_sched_barrier(0);
-        // every read of this stage has been issued: wait for them (lgkmcnt 0) and for tile kt+1
-        // (all but the ST-2 most recent tiles' loads), then synchronise
         wait_cnt<LPT*(ST - 2), 0>();
         __syncthreads();
         issue_loads(kt + ST, st);
         if (kt + 1 < nk) fetch(nst, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        mma(1);
+        mma(1, 1);
         __builtin_amdgcn_sched_barrier(0);
         st = nst;
     }
+#undef EXE_STEP
     wait_cnt<0, 15>();     // drain the tail loads before the workgroup's LDS is released
 
     // accumulator layout: element r of lane l is (n = 8*(r/4) + 4*(l/32) + r%4, m = l%32) of its 32x32 tile
