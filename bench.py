@@ -172,6 +172,9 @@ def main():
                     help="opt13b is the benchmark (BASELINE metric); the others are secondary measurements")
     ap.add_argument("--decode-batch", type=int, default=0, help="B0: sequences decoded together (default per workload)")
     ap.add_argument("--layers", type=int, default=0, help="debugging only: fewer layers is NOT the benchmark")
+    ap.add_argument("--rra", type=int, default=0, metavar="N_D",
+                    help="also run the refilled (RRA) schedule: 3 x B0 requests, decode batch B0, N_D decode iterations "
+                         "between encoding phases (secondary figures under the key \"rra\")")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -212,6 +215,8 @@ def main():
         need_tokens = int(((job.in_len + job.out_len + 8) // 8 * 8).sum())
     else:
         need_tokens = int(((job.in_len + 8) // 8 * 8).sum() + ((job.out_len + 8) // 8 * 8).sum())
+    if args.rra:
+        need_tokens = int(need_tokens * 1.3)          # refilled batches fragment the pool: leave slack
     cfg = exe.config_from_shape(shape, kv_pool_bytes=need_tokens * kv_tok, max_seqs=job.n,
                                 max_batch_tokens=job.encode_batch * max_in, max_batch_seqs=max(job.n, job.encode_batch))
     stream = torch.cuda.Stream()
@@ -278,6 +283,16 @@ def main():
         out["roofline_decode_sampling"] = f"decode classes timed on every {every}th iteration"
         enc_flops = sum(a["flops"] for a in acc["encode"].values())
         out["encode_frac_of_mfma_peak"] = round(enc_flops / (t_enc / K) / PEAK_MFMA_BF16, 4)
+    if args.rra and shape.has_embed:
+        rng = np.random.default_rng(wl.BASE_SEED + 17)
+        big = {"opt13b": wl.workload_opt13b, "t5_11b": wl.workload_t5}[args.workload](3 * job.n, seed=wl.BASE_SEED + 17)
+        _, st = m.run_rra(job.n, args.rra, big.in_len, big.out_len, big.tokens, max_encode_batch=job.encode_batch)
+        out["rra"] = {"schedule": f"RRA, {big.n} requests queued at time 0, decode batch {job.n}, N_D = {args.rra}, "
+                                  f"encode batches of at most {job.encode_batch}",
+                      "tokens_per_s": round((st["encoded_tokens"] + st["generated_tokens"]) / st["wall_s"], 1),
+                      "generated_tokens_per_s": round(st["generated_tokens"] / st["wall_s"], 1),
+                      "sequences_per_s": round(big.n / st["wall_s"], 2),
+                      **{k: (round(v, 4) if isinstance(v, float) else v) for k, v in st.items()}}
     if not args.no_cpu_baseline:
         cb = cpu_baseline(shape, weights, job)
         if cb:

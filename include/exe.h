@@ -169,6 +169,37 @@ int exe_profile(exe_model_t* m, int32_t phase, const int32_t* batch_sizes, int32
                 int32_t n_steps, exe_profile_row_t* rows, int32_t rows_cap, int32_t* n_rows);
 
 /*
+ * RRA schedule on one GPU (Section 4 "RRA Scheduling": encode once, then decode for N_D iterations, repeatedly;
+ * the encoding batch B_E equals the number of queries completed in the previous N_D decoding iterations, which
+ * keeps the decoding batch near B_D; Section 5 "dynamic workload adjustment": the sum of input lengths of an
+ * encoding batch is kept within a tolerance of the average encoder workload).
+ * All n_requests are queued at time 0 and served first-come first-served with forced output lengths (Section 7:
+ * decoding continues for the given length, no end-of-sequence token); finished sequences leave the decode
+ * batch at once (early termination).  Needs a model with token embedding and LM head and no live sequence;
+ * uses sequence ids 0 .. decode_batch-1.
+ *  input_lengths, output_lengths [n_requests] host (output_lengths >= 1); tokens_packed [sum input_lengths] host.
+ *  out_tokens [sum output_lengths] host, nullable: the generated tokens, request after request.
+ */
+typedef struct exe_rra_config {
+    int32_t decode_batch;        /* B_D: live sequences the schedule keeps in the decode batch */
+    int32_t n_decode;            /* N_D: decode iterations between two encoding phases */
+    int32_t max_encode_batch;    /* most sequences per exe_encode call (<= max_batch_seqs) */
+    int32_t adjust;              /* 1: dynamic workload adjustment of the encoding batch */
+    float workload_tolerance;    /* adjust: an encoding phase takes at most (1 + tol) * B_E * mean input length tokens */
+} exe_rra_config_t;
+typedef struct exe_rra_stats {
+    double wall_s, encode_s, decode_s;
+    int64_t encoded_tokens, generated_tokens;
+    int32_t encode_phases, encode_calls, decode_iterations;
+    double mean_decode_batch;                 /* over decode iterations */
+    double latency_mean_s, latency_p50_s, latency_p99_s, latency_max_s;   /* admission (encode start) -> last token */
+    double queue_p99_s;                       /* time 0 -> admission */
+} exe_rra_stats_t;
+int exe_run_rra(exe_model_t* m, const exe_rra_config_t* cfg, int32_t n_requests, const int32_t* input_lengths,
+                const int32_t* output_lengths, const int32_t* tokens_packed, int32_t* out_tokens,
+                exe_rra_stats_t* stats);
+
+/*
  * Per-kernel-class timing (HIP events on the model's stream around every launch of the class) with the
  * algorithmic bytes and flops of those launches; used to report achieved GB/s or TFLOP/s.
  * Enabling it serialises nothing but adds two event records per launch.

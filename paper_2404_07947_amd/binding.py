@@ -12,7 +12,7 @@ _lib = None
 
 DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
-    "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_profile", "exe_kernel_timing",
+    "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_profile", "exe_run_rra", "exe_kernel_timing",
     "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_norm", "exe_op_prefill_attention",
     "exe_op_decode_attention", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
 ]
@@ -49,6 +49,19 @@ class LengthDist(C.Structure):
                 ("hi", C.c_int32), ("seed", C.c_uint64)]
 
 
+class RraConfig(C.Structure):
+    _fields_ = [("decode_batch", C.c_int32), ("n_decode", C.c_int32), ("max_encode_batch", C.c_int32),
+                ("adjust", C.c_int32), ("workload_tolerance", C.c_float)]
+
+
+class RraStats(C.Structure):
+    _fields_ = [("wall_s", C.c_double), ("encode_s", C.c_double), ("decode_s", C.c_double),
+                ("encoded_tokens", C.c_int64), ("generated_tokens", C.c_int64), ("encode_phases", C.c_int32),
+                ("encode_calls", C.c_int32), ("decode_iterations", C.c_int32), ("mean_decode_batch", C.c_double),
+                ("latency_mean_s", C.c_double), ("latency_p50_s", C.c_double), ("latency_p99_s", C.c_double),
+                ("latency_max_s", C.c_double), ("queue_p99_s", C.c_double)]
+
+
 class KernelTime(C.Structure):
     _fields_ = [("kind", C.c_int32), ("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double),
                 ("flops", C.c_double)]
@@ -77,6 +90,7 @@ def lib():
     L.exe_seq_length.argtypes = [vp, i32]
     L.exe_kv_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), ip]
     L.exe_profile.argtypes = [vp, i32, ip, i32, ip, i32, C.POINTER(LengthDist), i32, C.POINTER(ProfileRow), i32, ip]
+    L.exe_run_rra.argtypes = [vp, C.POINTER(RraConfig), i32, ip, ip, ip, ip, C.POINTER(RraStats)]
     L.exe_kernel_timing.argtypes = [vp, i32]
     L.exe_kernel_times.argtypes = [vp, C.POINTER(KernelTime)]
     L.exe_op_gemm.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i32, C.c_float, i32, vp, vp, C.c_uint64]
@@ -207,6 +221,16 @@ class Model:
         _check(lib().exe_profile(self._h, phase, _ip(bs), len(bs), _ip(ls), len(ls),
                                  C.byref(dist) if dist is not None else None, n_steps, rows, cap, C.byref(n)))
         return [{f: getattr(rows[i], f) for f, _ in ProfileRow._fields_} for i in range(n.value)]
+
+    def run_rra(self, decode_batch: int, n_decode: int, input_lengths, output_lengths, tokens_packed,
+                max_encode_batch: int = 32, adjust: bool = False, workload_tolerance: float = 0.25):
+        """Returns (generated tokens packed request after request, stats dict)."""
+        il, ol, tk = _i32(input_lengths), _i32(output_lengths), _i32(tokens_packed)
+        out = np.zeros(int(ol.sum()), dtype=np.int32)
+        cfg = RraConfig(decode_batch, n_decode, max_encode_batch, int(adjust), workload_tolerance)
+        st = RraStats()
+        _check(lib().exe_run_rra(self._h, C.byref(cfg), len(il), _ip(il), _ip(ol), _ip(tk), _ip(out), C.byref(st)))
+        return out, {f: getattr(st, f) for f, _ in RraStats._fields_}
 
     def kernel_timing(self, enable: bool) -> None:
         _check(lib().exe_kernel_timing(self._h, int(enable)))

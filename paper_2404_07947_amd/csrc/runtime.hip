@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <map>
 #include <string>
@@ -1098,6 +1099,162 @@ extern "C" int exe_profile(exe_model_t* m, int32_t phase, const int32_t* batch_s
             if (r) return r;
             ++*n_rows;
         }
+    return EXE_OK;
+}
+
+// ---------------------------------------------------------------- RRA schedule (single GPU)
+static double now_s()
+{
+    return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+extern "C" int exe_run_rra(exe_model_t* m, const exe_rra_config_t* cfg, int32_t n_requests, const int32_t* input_lengths,
+                           const int32_t* output_lengths, const int32_t* tokens_packed, int32_t* out_tokens,
+                           exe_rra_stats_t* stats)
+{
+    if (!m || !cfg || !input_lengths || !output_lengths || !tokens_packed || !stats) return fail(EXE_ERR_ARG, "null argument");
+    const exe_config_t& c = m->c;
+    if (!c.has_embed || !c.has_lm_head) return fail(EXE_ERR_SHAPE, "exe_run_rra needs token embedding and LM head");
+    if (m->live > 0) return fail(EXE_ERR_BAD_SEQ, "exe_run_rra needs a model with no live sequence");
+    if (n_requests < 1 || cfg->decode_batch < 1 || cfg->n_decode < 1 || cfg->max_encode_batch < 1)
+        return fail(EXE_ERR_ARG, "bad schedule parameters");
+    if (cfg->decode_batch > c.max_batch_seqs || cfg->decode_batch > c.max_seqs || cfg->max_encode_batch > c.max_batch_seqs)
+        return fail(EXE_ERR_ARG, "decode_batch / max_encode_batch exceed the model's limits");
+    bool dec_only = c.arch == EXE_ARCH_DECODER_ONLY;
+    std::vector<int64_t> tok_off(n_requests + 1, 0), out_off(n_requests + 1, 0);
+    double mean_in = 0;
+    for (int i = 0; i < n_requests; ++i) {
+        if (input_lengths[i] < 1 || output_lengths[i] < 1) return fail(EXE_ERR_BAD_LENGTH, "request %d has an empty input or output", i);
+        tok_off[i + 1] = tok_off[i] + input_lengths[i];
+        out_off[i + 1] = out_off[i] + output_lengths[i];
+        mean_in += input_lengths[i];
+    }
+    mean_in /= n_requests;
+
+    const int BD = cfg->decode_batch;
+    std::vector<int> slot_req(BD, -1), slot_done(BD, 0), slot_tok(BD, 0);   // request in a slot, tokens produced, last token
+    std::vector<int> free_slots;
+    for (int s = BD - 1; s >= 0; --s) free_slots.push_back(s);
+    std::vector<double> t_admit(n_requests, 0.0), t_finish(n_requests, 0.0);
+    memset(stats, 0, sizeof(*stats));
+    int next_req = 0, finished = 0, live = 0;
+    int completed_since_encode = BD;      // the first encoding phase fills the whole decode batch
+    double batch_sum = 0;
+    double t0 = now_s();
+
+    auto emit = [&](int slot, int token, double t) -> bool {   // records a generated token; true if the request is done
+        int r = slot_req[slot];
+        if (out_tokens) out_tokens[out_off[r] + slot_done[slot]] = token;
+        slot_tok[slot] = token;
+        slot_done[slot] += 1;
+        stats->generated_tokens += 1;
+        if (slot_done[slot] < output_lengths[r]) return false;
+        t_finish[r] = t;
+        return true;
+    };
+    auto retire = [&](const std::vector<int>& slots) -> int {
+        if (slots.empty()) return EXE_OK;
+        int r = exe_seq_release(m, (int)slots.size(), slots.data());
+        if (r) return r;
+        for (int s : slots) { slot_req[s] = -1; free_slots.push_back(s); --live; ++finished; ++completed_since_encode; }
+        return EXE_OK;
+    };
+
+    std::vector<int32_t> ids, lens, res, toks, kv, nxt;
+    while (finished < n_requests) {
+        // ---- encoding phase: B_E = queries completed during the previous decoding phase
+        int want = std::min(completed_since_encode, BD - live);
+        want = std::min(want, n_requests - next_req);
+        double budget = cfg->adjust ? (1.0 + cfg->workload_tolerance) * std::max(1, want) * mean_in : 1e300;
+        double taken = 0;
+        if (want > 0) stats->encode_phases += 1;
+        completed_since_encode = 0;
+        while (want > 0) {
+            ids.clear(); lens.clear(); res.clear();
+            int64_t first_tok = tok_off[next_req], T = 0;
+            int first_req = next_req;
+            while (want > 0 && (int)ids.size() < cfg->max_encode_batch && next_req < n_requests) {
+                int L = input_lengths[next_req];
+                if (T + L > c.max_batch_tokens) break;
+                if (!ids.empty() || taken > 0) if (taken + L > budget) { want = 0; break; }   // workload adjustment
+                int s = free_slots.back();
+                free_slots.pop_back();
+                ids.push_back(s); lens.push_back(L);
+                res.push_back(dec_only ? L + output_lengths[next_req] : output_lengths[next_req]);
+                slot_req[s] = next_req; slot_done[s] = 0;
+                T += L; taken += L;
+                ++next_req; --want;
+            }
+            if (ids.empty()) {
+                if (next_req < n_requests && input_lengths[next_req] > c.max_batch_tokens)
+                    return fail(EXE_ERR_ARG, "request %d is longer than max_batch_tokens", next_req);
+                break;
+            }
+            nxt.assign(ids.size(), 0);
+            double ta = now_s();
+            int r = exe_encode(m, (int)ids.size(), ids.data(), lens.data(), tokens_packed + first_tok, res.data(), nullptr,
+                               dec_only ? nxt.data() : nullptr, nullptr);
+            if (r == EXE_ERR_OOM_KV && live > 0) {
+                // the pool cannot take this batch yet: put the requests back and decode on; sequences that
+                // finish will free their extents before the next encoding phase
+                for (int s : ids) { slot_req[s] = -1; free_slots.push_back(s); }
+                next_req = first_req;
+                break;
+            }
+            if (r) return r;
+            double tb = now_s();
+            stats->encode_s += tb - ta;
+            stats->encode_calls += 1;
+            stats->encoded_tokens += T;
+            live += (int)ids.size();
+            std::vector<int> done;
+            for (size_t k = 0; k < ids.size(); ++k) {
+                t_admit[first_req + k] = ta - t0;
+                if (dec_only) { if (emit(ids[k], nxt[k], tb - t0)) done.push_back(ids[k]); }
+                else slot_tok[ids[k]] = 0;                    // encoder-decoder: decoding starts from token id 0
+            }
+            if ((r = retire(done))) return r;
+        }
+        if (live == 0) {
+            if (next_req >= n_requests) break;
+            completed_since_encode = BD;                      // nothing to decode: go straight to the next encoding phase
+            continue;
+        }
+        // ---- decoding phase: N_D iterations over the live batch
+        for (int it = 0; it < cfg->n_decode && live > 0; ++it) {
+            ids.clear(); toks.clear(); kv.clear();
+            for (int s = 0; s < BD; ++s) {
+                if (slot_req[s] < 0) continue;
+                ids.push_back(s);
+                toks.push_back(slot_tok[s]);
+                int r = slot_req[s];
+                kv.push_back(dec_only ? input_lengths[r] + slot_done[s] : slot_done[s] + 1);
+            }
+            nxt.assign(ids.size(), 0);
+            double ta = now_s();
+            int r = exe_decode_step(m, (int)ids.size(), ids.data(), toks.data(), kv.data(), nullptr, nxt.data(), nullptr);
+            if (r) return r;
+            double tb = now_s();
+            stats->decode_s += tb - ta;
+            stats->decode_iterations += 1;
+            batch_sum += (double)ids.size();
+            std::vector<int> done;
+            for (size_t k = 0; k < ids.size(); ++k)
+                if (emit(ids[k], nxt[k], tb - t0)) done.push_back(ids[k]);
+            if ((r = retire(done))) return r;
+        }
+    }
+    stats->wall_s = now_s() - t0;
+    stats->mean_decode_batch = stats->decode_iterations ? batch_sum / stats->decode_iterations : 0.0;
+    std::vector<double> lat(n_requests), q(n_requests);
+    for (int i = 0; i < n_requests; ++i) { lat[i] = t_finish[i] - t_admit[i]; q[i] = t_admit[i]; stats->latency_mean_s += lat[i] / n_requests; }
+    std::sort(lat.begin(), lat.end());
+    std::sort(q.begin(), q.end());
+    auto pct = [&](const std::vector<double>& v, double p) { return v[std::min<size_t>(v.size() - 1, (size_t)(p * v.size()))]; };
+    stats->latency_p50_s = pct(lat, 0.50);
+    stats->latency_p99_s = pct(lat, 0.99);
+    stats->latency_max_s = lat.back();
+    stats->queue_p99_s = pct(q, 0.99);
     return EXE_OK;
 }
 
