@@ -275,24 +275,37 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t* __restr
                 s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, qf[kk], s_acc[t], 0, 0, 0);
             }
         }
-        // element r of lane (qi, g) in s_acc[t]: key = kt*64 + t*32 + 8*(r/4) + 4*g + r%4, query qpos
+        // element r of lane (qi, g) in s_acc[t]: key = kt*64 + t*32 + 8*(r/4) + 4*g + r%4, query qpos.
+        // Only tiles that straddle the sequence end or (causal) this wave's diagonal need the per-element mask.
+        bool edge = kt * PF_KT + PF_KT > n || (CAUSAL && kt * PF_KT + PF_KT - 1 > q0 + wave * 32);
         float mx = -INFINITY;
+        if (BIAS || edge) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int key = kt * PF_KT + t * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                float v = s_acc[t][r] * sc;
-                if (BIAS) {
-                    int rel = key - qpos;
-                    rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
-                    v += sbias[rel + radius];
+                for (int r = 0; r < 16; ++r) {
+                    int key = kt * PF_KT + t * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    float v = s_acc[t][r] * sc;
+                    if (BIAS) {
+                        int rel = key - qpos;
+                        rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
+                        v += sbias[rel + radius];
+                    }
+                    bool ok = key < n && (!CAUSAL || key <= qpos);
+                    v = ok ? v : -INFINITY;
+                    s_acc[t][r] = v;
+                    mx = fmaxf(mx, v);
                 }
-                bool ok = key < n && (!CAUSAL || key <= qpos);
-                v = ok ? v : -INFINITY;
-                s_acc[t][r] = v;
-                mx = fmaxf(mx, v);
-            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v = s_acc[t][r] * sc;
+                    s_acc[t][r] = v;
+                    mx = fmaxf(mx, v);
+                }
+        }
         mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
         float m_new = fmaxf(m_run, mx);
         float mref = m_new == -INFINITY ? 0.f : m_new;
@@ -309,10 +322,13 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t* __restr
         rs += __shfl_xor(rs, 32, WAVE);
         l_run = l_run * alpha + rs;
         m_run = m_new;
+        // the running maximum of a query stops moving after the first tiles: rescale only when some lane needs it
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+            for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o_acc[ct][r] *= alpha;
+                for (int r = 0; r < 16; ++r) o_acc[ct][r] *= alpha;
+        }
 
         // O^T += V^T . P^T.  MFMA k-step ks covers, in lane group g, the 8 keys held in accumulator
         // elements 8*(ks%2) .. +7 of s_acc[ks/2]: key groups kq = (ks/2)*8 + (ks%2)*4 + g and kq + 2.
