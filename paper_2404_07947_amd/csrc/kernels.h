@@ -46,6 +46,10 @@ struct AttnCacheArgs {       // one query row per batch entry against that seque
     float scale;
     const float* bias_by_dist; int bias_radius;   // [H, 2r+1] or nullptr
     void* out;                             // [B, H*dh]
+    // fused append (optional): the new position's key / value rows of (b, head) are at
+    // q + b*q_stride + new_k_off + head*dh and ... + new_v_off; the kernel stores them at position len-1 of the
+    // cache and attends to them straight from there (new_k_off = 0 disables)
+    int new_k_off = 0, new_v_off = 0;
 };
 hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s);
 

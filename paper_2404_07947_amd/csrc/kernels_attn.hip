@@ -37,10 +37,10 @@ template <> struct Chunk<bf16_t, 8> {
 
 template <typename T, int DH, bool PACKED, int NWV = 4, int U = 4>
 __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
-    const T* __restrict__ q, int q_stride, const T* __restrict__ kvbuf, const int64_t* __restrict__ base,
+    const T* __restrict__ q, int q_stride, const T* kvbuf, const int64_t* __restrict__ base,
     const int32_t* __restrict__ cap, const int32_t* __restrict__ len, const int32_t* __restrict__ qpos_arr,
     const int32_t* __restrict__ tok_b, const int32_t* __restrict__ cu, int layer, int H, int causal, float scale,
-    const float* __restrict__ bias_by_dist, int radius, T* __restrict__ out)
+    const float* __restrict__ bias_by_dist, int radius, T* __restrict__ out, int new_k_off, int new_v_off)
 {
     constexpr int EPL = 16 / sizeof(T);      // elements per 16-byte chunk
     constexpr int LPR = DH / EPL;            // lanes that share one key/value row
@@ -75,6 +75,18 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
         vp = kp + (int64_t)H * c * DH;
         qp = q + (int64_t)r * q_stride + h * DH;
     }
+    // Fused append: the newest position's key/value rows come from the projection output; one 16-lane group
+    // stores them into the cache, and every lane that meets row nk-1 reads it from the source instead of the
+    // cache, so no ordering between that store and the loads is needed.
+    const T *knew = nullptr, *vnew = nullptr;
+    if (!PACKED && new_k_off) {
+        knew = qp + new_k_off;
+        vnew = qp + new_v_off;
+        if (wave == 0 && rg == 0) {
+            *(uint4*)(const_cast<T*>(kp) + (int64_t)(nk - 1) * DH + cl * EPL) = *(const uint4*)(knew + cl * EPL);
+            *(uint4*)(const_cast<T*>(vp) + (int64_t)(nk - 1) * DH + cl * EPL) = *(const uint4*)(vnew + cl * EPL);
+        }
+    }
 
     float qf[EPL];
     {
@@ -96,8 +108,11 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
         for (int u = 0; u < U; ++u) {
             int j = j0 + u * RPW + rg;
             int jj = j < nk ? j : nk - 1;
-            kc[u] = *(const uint4*)(kp + (int64_t)jj * row_stride + cl * EPL);
-            vc[u] = *(const uint4*)(vp + (int64_t)jj * row_stride + cl * EPL);
+            const T* kr = kp + (int64_t)jj * row_stride;
+            const T* vr = vp + (int64_t)jj * row_stride;
+            if (!PACKED && knew && jj == nk - 1) { kr = knew; vr = vnew; }
+            kc[u] = *(const uint4*)(kr + cl * EPL);
+            vc[u] = *(const uint4*)(vr + cl * EPL);
         }
         float mx = m_run;
 #pragma unroll
@@ -164,7 +179,7 @@ hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s)
     attn_row_kernel<T, DH, false, 16, 2><<<grid, 1024, 0, s>>>((const T*)a.q, a.q_stride, (const T*)a.pool,     \
                                                                a.base, a.cap, a.len, a.qpos, nullptr, nullptr,  \
                                                                a.layer, a.H, 0, a.scale, a.bias_by_dist,        \
-                                                               a.bias_radius, (T*)a.out)
+                                                               a.bias_radius, (T*)a.out, a.new_k_off, a.new_v_off)
     if (a.dtype == DT_F32 && a.dh == 64) EXE_ROW(float, 64);
     else if (a.dtype == DT_F32 && a.dh == 128) EXE_ROW(float, 128);
     else if (a.dtype == DT_BF16 && a.dh == 64) EXE_ROW(bf16_t, 64);
@@ -387,7 +402,7 @@ hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s)
 #define EXE_ROW(T, DH)                                                                                           \
     attn_row_kernel<T, DH, true><<<grid, 256, 0, s>>>(nullptr, 0, (const T*)a.qkv, nullptr, nullptr, nullptr,    \
                                                       a.tok_pos, a.tok_b, a.cu, 0, a.H, a.causal, a.scale,       \
-                                                      a.bias_by_dist, a.bias_radius, (T*)a.out)
+                                                      a.bias_by_dist, a.bias_radius, (T*)a.out, 0, 0)
     if (a.dtype == DT_F32 && a.dh == 64) EXE_ROW(float, 64);
     else if (a.dtype == DT_F32 && a.dh == 128) EXE_ROW(float, 128);
     else if (a.dtype == DT_BF16 && a.dh == 64) EXE_ROW(bf16_t, 64);

@@ -787,13 +787,16 @@ static int decode_layer(exe_model* m, const DecLayerW& L, int layer, int n, cons
     if (parts & 1) {
         if ((r = run_norm(m, nullptr, n, L.n1_g, L.n1_b, 1.f, m->a))) return r;
         if ((r = run_gemm(m, n, 3 * m->inner, c.d_model, m->a, L.w_qkv, L.b_qkv, -1, 1.f, OUT_T, m->qkv))) return r;
-        LAUNCH(m, EXE_K_OTHER, 4.0 * n * m->inner * e, 0.0,
-               launch_kv_append(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, n, nullptr, d.pos, d.base, d.cap,
-                                layer, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
+        if (!(parts & 2))      // the attention kernel appends the new key/value rows itself when it runs
+            LAUNCH(m, EXE_K_OTHER, 4.0 * n * m->inner * e, 0.0,
+                   launch_kv_append(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, n, nullptr, d.pos, d.base, d.cap,
+                                    layer, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
     }
     if (parts & 2) {
         AttnCacheArgs a{c.dtype, n, c.n_heads, c.head_dim, m->qkv, 3 * m->inner, m->pool.ptr, d.base, d.cap, d.len, d.pos,
                         layer, attn_scale(m), encdec ? m->bias_dec : nullptr, m->radius, m->ctx};
+        a.new_k_off = m->inner;
+        a.new_v_off = 2 * m->inner;
         LAUNCH(m, EXE_K_DECODE_ATTN, d.self_bytes, d.self_flops, launch_attn_cache(a, m->stream));
     }
     if (parts & 1)
