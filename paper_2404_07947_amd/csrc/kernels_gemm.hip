@@ -1,6 +1,6 @@
 // GEMM kernels for the projections of a Transformer layer: out = epilogue(alpha * A[M,K] . W[N,K]^T + bias).
 //
-//  * gemm_tile_kernel    bf16, MFMA 32x32x16.  Macro tiles (BM x 256 or BM x 128, 64 k per LDS stage) filled by
+//  * gemm_tile_kernel    bf16, MFMA 16x16x32.  Macro tiles (BM x 256 or BM x 128, 64 k per LDS stage) filled by
 //                        direct global->LDS loads into a ring of stages; software-pipelined fragment fetch;
 //                        optional split-K into float partials, finished by splitk_reduce_kernel.
 //                        Large M (encode) is MFMA / LDS-fill bound; small M (decode) streams the weights.
@@ -47,7 +47,7 @@ __device__ __forceinline__ void epilogue_store4(f32x4 v, int m, int n, int N, co
     }
 }
 
-// ---------------------------------------------------------------- tile kernel (bf16, MFMA 32x32x16)
+// ---------------------------------------------------------------- tile kernel (bf16, MFMA 16x16x32): LDS layout
 // LDS tile layout for a stage of 64 bf16 along K: row r is 128 bytes = 8 chunks of 16 bytes; chunk c is
 // stored at slot c ^ ((r>>1)&7), so that 16 consecutive rows read at the same chunk index touch 16 distinct
 // 16-byte bank groups (256 bytes of banks; measured: zero LDS bank conflicts).
@@ -65,174 +65,346 @@ template <int N, int L> __device__ __forceinline__ void wait_cnt()
     __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14) | (L << 8));
 }
 
+// ---------------------------------------------------------------- tile epilogue
+// A lane of a 16x16 accumulator tile holds 4 consecutive output features n = 4*(l/16) .. +3 of one row m = l%16:
+// stored as it lies, a wave-wide store would scatter 16-byte pieces over 16 output rows.  Each wave therefore
+// turns its tiles through a private LDS buffer, a "group" of 32 rows x EN columns (2 x EN/16 tiles) at a time,
+// with the 16-byte slots XOR-swizzled by row so that neither side has bank conflicts, and then stores whole
+// row segments.
+//
+// The LDS accesses are written as inline assembly on purpose: the compiler assumes that a DS read may alias the
+// destination of the direct global->LDS loads still in flight for the next item and would put a vmcnt(0) in
+// front of every one of them, which also waits for the stores of the previous group.  The buffer is private to
+// the wave and is never a destination of those loads; DS operations of one wave execute in order, and the
+// lgkmcnt(0) after the reads completes them before the next group's writes.
+enum EpiMode { EPI_PARTIAL = 0, EPI_F32, EPI_RESID, EPI_T, EPI_T_RELU, EPI_T_GELU };
+
+template <int QW> struct LdsTurn;
+template <> struct LdsTurn<4> {
+    static __device__ __forceinline__ void read(f32x4 (&v)[4], const unsigned (&a)[4])
+    {
+        asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+                     : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3])
+                     : "memory");
+    }
+};
+template <> struct LdsTurn<2> {
+    static __device__ __forceinline__ void read(f32x4 (&v)[2], const unsigned (&a)[2])
+    {
+        asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(v[0]), "=&v"(v[1])
+                     : "v"(a[0]), "v"(a[1])
+                     : "memory");
+    }
+};
+
+// acc[i][j]: the wave's accumulator tiles (i: 16 output features, j: 16 rows); stg: LDS byte address of the wave's
+// buffer (EN * 128 bytes); (row0, col0): output coordinates of the wave's first element; fout: float destination
+// of EPI_PARTIAL / EPI_F32 / EPI_RESID; tout: bf16 destination of EPI_T*.
+template <int TM, int TN, int EN, int MODE>
+__device__ __forceinline__ void epilogue_tiles(const f32x4 (&acc)[TN][TM], unsigned stg, int lane, int row0, int col0,
+                                               int M, int N, const bf16_t* __restrict__ bias, float alpha,
+                                               float* __restrict__ fout, bf16_t* __restrict__ tout)
+{
+    static_assert(TM % 2 == 0 && TN % 2 == 0, "groups are 2 tiles high");
+    constexpr int QW = EN / 8;                  // 16-byte slots a lane writes, and reads, per group
+    constexpr int IW = EN / 16;                 // tiles side by side in a group
+    constexpr int NG = TN / IW;                 // groups per 32 rows
+    constexpr int G = (TM / 2) * NG;
+    constexpr int RPP = EN == 32 ? 8 : 16;      // output rows covered by one wave-wide read
+    constexpr int D = G < 2 ? G : 2;            // residual prefetch depth in groups (registers: D * QW * 4)
+    int lm = lane & 15, lq = lane >> 4;
+    int rc = EN == 32 ? (lane & 7) : (lane & 3);
+    int rr = EN == 32 ? (lane >> 3) : (lane >> 2);
+    // slot of (row m, 16-byte column c) in the buffer
+    auto slot = [](int m, int c) { return EN == 32 ? m * 8 + (c ^ ((m >> 1) & 7)) : m * 4 + (c ^ ((m >> 2) & 3)); };
+    unsigned waddr[QW], raddr[QW];
+#pragma unroll
+    for (int x = 0; x < QW; ++x) {
+        int jj = x / IW, ii = x % IW;           // tile (ii, jj) of the group
+        waddr[x] = stg + slot(jj * 16 + lm, ii * 4 + lq) * 16;
+        raddr[x] = stg + slot(x * RPP + rr, rc) * 16;
+    }
+    // group g = jp * NG + ig covers rows row0 + 32 jp .. +31 and columns col0 + EN ig .. + EN - 1
+    auto g_row = [&](int g, int p) { return row0 + (g / NG) * 32 + p * RPP + rr; };
+    auto g_col = [&](int g) { return col0 + (g % NG) * EN + rc * 4; };
+    f32x4 bv[NG];
+    if (MODE != EPI_PARTIAL) {
+#pragma unroll
+        for (int x = 0; x < NG; ++x) {
+            int n = g_col(x);
+            bv[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (bias && n < N) {
+                bf16x4 b = *(const bf16x4*)(bias + n);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bv[x][e] = (float)b[e];
+            }
+        }
+    }
+    f32x4 res[D][QW];
+    auto load_res = [&](int g) {
+        int n = g_col(g);
+#pragma unroll
+        for (int p = 0; p < QW; ++p) {
+            int m = g_row(g, p);
+            res[g % D][p] = (m < M && n < N) ? *(const f32x4*)(fout + (int64_t)m * N + n) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    if (MODE == EPI_RESID) {
+#pragma unroll
+        for (int g = 0; g < D; ++g) load_res(g);
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        int jp = g / NG, ig = g % NG;
+#pragma unroll
+        for (int x = 0; x < QW; ++x) {
+            f32x4 vv = acc[ig * IW + x % IW][jp * 2 + x / IW];
+            asm volatile("ds_write_b128 %0, %1" ::"v"(waddr[x]), "v"(vv) : "memory");
+        }
+        f32x4 v[QW];
+        LdsTurn<QW>::read(v, raddr);
+        int n = g_col(g);
+#pragma unroll
+        for (int p = 0; p < QW; ++p) {
+            int m = g_row(g, p);
+            if (m >= M || n >= N) continue;
+            int64_t o = (int64_t)m * N + n;
+            if (MODE == EPI_PARTIAL) {
+                *(f32x4*)(fout + o) = v[p];
+            } else {
+                f32x4 r = v[p] * alpha + bv[ig];
+                if (MODE == EPI_F32) *(f32x4*)(fout + o) = r;
+                else if (MODE == EPI_RESID) *(f32x4*)(fout + o) = res[g % D][p] + r;
+                else {
+                    bf16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        w[e] = (bf16_t)(MODE == EPI_T_RELU ? act_apply(r[e], 0) : MODE == EPI_T_GELU ? act_apply(r[e], 1) : r[e]);
+                    *(bf16x4*)(tout + o) = w;
+                }
+            }
+        }
+        if (MODE == EPI_RESID && g + D < G) load_res(g + D);
+        __builtin_amdgcn_sched_barrier(0);      // keeps the groups in order: hoisted loads would cost registers
+    }
+}
+
+// Columns that a wave turns through LDS at a time in the epilogue: 32 (4 KB per wave) where the stages leave
+// room within the 160 KB of a CU, else 16 (2 KB per wave).
+constexpr int epilogue_cols(int BM, int BN, int WM, int WN, int ST)
+{
+    return ST * (BM + BN) * TBK * 2 + (BM / WM) * (BN / WN) * 4096 <= 160 * 1024 ? 32 : 16;
+}
+
+// ---------------------------------------------------------------- tile kernel
 // Tiles are filled with direct global->LDS loads (no staging registers): one wave-wide 16-byte load
 // writes 1 KB of consecutive tile rows, lane l landing at byte 16*l.  The swizzle is therefore applied on
 // the global side: lane l fetches chunk (l % 8) ^ swz(row) of row l / 8.
 //
-// ST LDS stages of 64 k form a ring: while tile kt is multiplied, tiles kt+1 .. kt+ST-1 are in flight.
-// Inside a tile the loop is software-pipelined: the operand fragments of k-step ks+1 are fetched from LDS
-// while the MFMAs of step ks run.  The one barrier per tile sits after the last fragment fetch of the tile
-// (before its last MFMA group): behind it every wave has finished reading the current stage and tile kt+1
-// has landed, so the loads of tile kt+ST are issued into the stage just vacated and the first fragments of
-// tile kt+1 are fetched while the last MFMAs of tile kt execute.
+// ST LDS stages of 64 k form a ring: while k-tile kt is multiplied, k-tiles kt+1 .. kt+ST-1 are in flight.
+// Inside a k-tile the loop is software-pipelined over sub-steps (32 k x at most 64 rows of the wave's tile): the
+// operand fragments of sub-step s+1 are fetched from LDS between the two halves of the MFMAs of sub-step s.  The
+// one barrier per k-tile sits in the middle of its last sub-step: behind it every wave has finished reading the
+// current stage and k-tile kt+1 has landed, so the loads of k-tile kt+ST are issued into the stage just vacated
+// and the first fragments of k-tile kt+1 are fetched while the last MFMAs of k-tile kt execute.
 //
-// Split-K (gridDim.z > 1): every workgroup writes its float partial tile; splitk_reduce_kernel finishes.
+// The MFMA is the 16x16x32 one (4 passes).  Measured on MI355X: while a SIMD executes 32x32x16 MFMAs (8 passes)
+// back to back, vector memory instructions of the waves on it are hardly issued at all (a loader wave beside an
+// MFMA wave ran 20x slower), so the tile loads and the MFMAs of a k-tile ran one after the other; beside
+// back-to-back 16x16x32 MFMAs the same loads run at 92 % of their stand-alone rate, at an equal MFMA rate.
 //
-// Measured limits on MI355X (256x256 tile, 16384x15360x5120): MFMA loop alone 1.84 PFLOP/s, the
-// global->LDS path alone 2.2 PFLOP/s-equivalent (1.5 with a drain per tile); this kernel about 1.1-1.25.
+// Workgroups are persistent (one per CU) and the loader runs ahead across items, so that a tile's epilogue and
+// the first loads of the next tile overlap.  Split-K (n_split > 1): every item writes its float partial tile;
+// splitk_reduce_kernel finishes.
 template <int BM, int BN, int WM, int WN, int ST>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias,
     int act, float alpha, int out_mode, void* __restrict__ out, float* __restrict__ partial, int tiles_m, int tiles_n,
-    int k_per_split)
+    int k_per_split, int n_split)
 {
     constexpr int NW = (BM / WM) * (BN / WN);
-    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int TM = WM / 16, TN = WN / 16;       // 16x16 accumulator tiles of a wave: TM along rows, TN along features
+    constexpr int MH = TM > 4 ? TM / 4 : 1;         // row parts of the wave's tile, one per sub-step
+    constexpr int TMH = TM / MH;
+    constexpr int NS = 2 * MH;                      // sub-steps per k-tile
     constexpr int A_PASSES = BM / 8 / NW, B_PASSES = BN / 8 / NW;   // 1 KB wave-loads per wave per stage
     constexpr int LPT = A_PASSES + B_PASSES;
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "tile/waves mismatch");
     static_assert(LPT * (ST - 1) <= 63, "vmcnt range");
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int STAGE = (BM + BN) * TBK * 2;     // bytes per LDS stage: A tile then W tile
+    constexpr int EN = epilogue_cols(BM, BN, WM, WN, ST);
 
-    // workgroup -> tile: consecutive ids on one XCD (dispatch is round-robin over 8 XCDs) get a
-    // GM x (32/GM) patch of tiles so that the XCD's L2 sees each A and W tile a few times only.
+    // Work items are (split, output tile) pairs, numbered split-major.  The workgroups are persistent: workgroup b
+    // takes items b, b + gridDim.x, ...  Item -> tile: consecutive item numbers on one XCD (workgroups are
+    // dispatched round-robin over 8 XCDs and gridDim.x is a multiple of 8 whenever a workgroup takes more than
+    // one item) get a GM x (32/GM) patch of tiles so that the XCD's L2 sees each A and W tile a few times only.
     int total = tiles_m * tiles_n;
-    int pid = blockIdx.x;
-    int chunk = total / 8;
-    if (pid < chunk * 8) pid = (pid % 8) * chunk + pid / 8;
-    constexpr int GM = 8;
-    int group = pid / (GM * tiles_n);
-    int first_m = group * GM;
-    int gsz = tiles_m - first_m < GM ? tiles_m - first_m : GM;
-    int within = pid - group * GM * tiles_n;
-    int tile_m = first_m + within % gsz;
-    int tile_n = within / gsz;
-    int m0 = tile_m * BM, n0 = tile_n * BN;
-    int kbeg = blockIdx.z * k_per_split;
-    int kend = kbeg + k_per_split < K ? kbeg + k_per_split : K;
-    int nk = (kend - kbeg) / TBK;
+    int items = total * n_split;
+    auto locate = [&](int v, int& m0, int& n0, int& z) {
+        z = v / total;
+        int pid = v - z * total;
+        int chunk = total / 8;
+        if (pid < chunk * 8) pid = (pid % 8) * chunk + pid / 8;
+        constexpr int GM = 8;
+        int group = pid / (GM * tiles_n);
+        int first_m = group * GM;
+        int gsz = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+        int within = pid - group * GM * tiles_n;
+        m0 = (first_m + within % gsz) * BM;
+        n0 = (within / gsz) * BN;
+    };
+    auto k_tiles = [&](int z) {
+        int kbeg = z * k_per_split;
+        int kend = kbeg + k_per_split < K ? kbeg + k_per_split : K;
+        return (kend - kbeg) / TBK;
+    };
 
     int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int wm = wave % (BM / WM), wn = wave / (BM / WM);
 
-    // per-lane global source of each wave-load (row clamped into the matrix; rows past the edge are never stored)
-    const bf16_t* src_a[A_PASSES];
-    const bf16_t* src_w[B_PASSES];
+    // ---- loader: runs ST k-tiles ahead of the MFMA loop, across item boundaries.  The source of a wave-load is a
+    // uniform tile origin plus a per-lane byte offset (row clamped into the matrix; rows past the edge are never
+    // stored), which keeps the addresses in 8 registers.
+    unsigned off_a[A_PASSES], off_w[B_PASSES];
+    const char *base_a, *base_w;
+    int ld_v = blockIdx.x, ld_kt = 0, ld_nk = 1;
+    auto set_src = [&](int v) {
+        int m0, n0, z;
+        locate(v, m0, n0, z);
+        int kbeg = z * k_per_split;
+        ld_nk = k_tiles(z);
+        base_a = (const char*)(A + (int64_t)m0 * K + kbeg);
+        base_w = (const char*)(W + (int64_t)n0 * K + kbeg);
 #pragma unroll
-    for (int p = 0; p < A_PASSES; ++p) {
-        int rl = (p * NW + wave) * 8 + (lane >> 3);
-        int r = m0 + rl;
-        r = r < M ? r : M - 1;
-        src_a[p] = A + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz(rl)) << 3);
-    }
+        for (int p = 0; p < A_PASSES; ++p) {
+            int rl = (p * NW + wave) * 8 + (lane >> 3);
+            int r = m0 + rl < M ? rl : M - 1 - m0;
+            off_a[p] = (unsigned)r * (unsigned)(K * 2) + (((lane & 7) ^ lds_swz(rl)) << 4);
+        }
 #pragma unroll
-    for (int p = 0; p < B_PASSES; ++p) {
-        int rl = (p * NW + wave) * 8 + (lane >> 3);
-        int r = n0 + rl;
-        r = r < N ? r : N - 1;
-        src_w[p] = W + (int64_t)r * K + kbeg + (((lane & 7) ^ lds_swz(rl)) << 3);
-    }
-    // tile `kt` (clamped to the last one, which keeps the number of loads in flight uniform) -> stage
-    auto issue_loads = [&](int kt, int stage) {
-        kt = kt < nk ? kt : nk - 1;
-        unsigned char* base = lds + stage * STAGE;
-#pragma unroll
-        for (int p = 0; p < A_PASSES; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_a[p] + kt * TBK), (lds_ptr_t)(base + (p * NW + wave) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int p = 0; p < B_PASSES; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_w[p] + kt * TBK), (lds_ptr_t)(base + BM * TBK * 2 + (p * NW + wave) * 1024), 16, 0, 0);
-    };
-
-    f32x16 acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    int frow = lane & 31, fk = lane >> 5;
-    bf16x8 fa[2][TM], fw[2][TN];
-    auto fetch = [&](int stage, int ks, int b) {
-        const unsigned char* sa = lds + stage * STAGE;
-        const unsigned char* sw = sa + BM * TBK * 2;
-#pragma unroll
-        for (int j = 0; j < TM; ++j) fa[b][j] = *(const bf16x8*)(sa + lds_off(wm * WM + j * 32 + frow, ks * 2 + fk));
-#pragma unroll
-        for (int i = 0; i < TN; ++i) fw[b][i] = *(const bf16x8*)(sw + lds_off(wn * WN + i * 32 + frow, ks * 2 + fk));
-    };
-    // the MFMAs of one k-step in two halves, so that the next step's fragment fetch can be issued between them
-    auto mma = [&](int b, int half) {
-        constexpr int NM = TN * TM;
-#pragma unroll
-        for (int x = 0; x < NM; ++x) {
-            if ((x < NM / 2) != (half == 0) && NM > 1) continue;
-            if (NM == 1 && half == 1) continue;
-            int i = x / TM, j = x % TM;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[b][i], fa[b][j], acc[i][j], 0, 0, 0);
+        for (int p = 0; p < B_PASSES; ++p) {
+            int rl = (p * NW + wave) * 8 + (lane >> 3);
+            int r = n0 + rl < N ? rl : N - 1 - n0;
+            off_w[p] = (unsigned)r * (unsigned)(K * 2) + (((lane & 7) ^ lds_swz(rl)) << 4);
         }
     };
-    // one k-step: first half of the MFMAs, then the fetch of the following step, then the second half.  The
-    // fragments a step needs were requested half a step earlier, so the wait in front of its MFMAs covers
-    // only loads that have had time to return.
-#define EXE_STEP(b, fetch_stmt)                  \
-    __builtin_amdgcn_sched_barrier(0);           \
-    mma(b, 0);                                   \
-    __builtin_amdgcn_sched_barrier(0);           \
-    fetch_stmt;                                  \
-    __builtin_amdgcn_sched_barrier(0);           \
-    mma(b, 1);                                   \
-    __builtin_amdgcn_sched_barrier(0);
-
-    // prologue: tiles 0 .. ST-1 go to stages 0 .. ST-1; wait for tile 0 only
+    set_src(ld_v);
+    // issues the loader's current k-tile into `stage` and advances it; past the last item the last k-tile is
+    // loaded again, which keeps the number of loads in flight uniform
+    auto issue_next = [&](int stage) {
+        unsigned char* base = lds + stage * STAGE;
+        const char* ka = base_a + ld_kt * (TBK * 2);
+        const char* kw = base_w + ld_kt * (TBK * 2);
 #pragma unroll
-    for (int t = 0; t < ST; ++t) issue_loads(t, t);
+        for (int p = 0; p < A_PASSES; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ka + off_a[p]), (lds_ptr_t)(base + (p * NW + wave) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kw + off_w[p]), (lds_ptr_t)(base + BM * TBK * 2 + (p * NW + wave) * 1024), 16, 0, 0);
+        if (ld_kt + 1 < ld_nk) ++ld_kt;
+        else if (ld_v + (int)gridDim.x < items) {
+            ld_v += gridDim.x;
+            ld_kt = 0;
+            set_src(ld_v);
+        }
+    };
+
+    // MFMA operands (16x16x32): lane l holds row l%16 and the 8 k-values 8*(l/16) .. +7 of a 32-k step, i.e.
+    // 16-byte chunk 4*ks + l/16 of the stage row.  The W fragments of a 32-k step are kept for all its row parts.
+    f32x4 acc[TN][TM];
+    int frow = lane & 15, fk = lane >> 4;
+    bf16x8 fa[2][TMH], fw[2][TN];
+    // fragments of sub-step s of the k-tile in `stage`: activation rows of its row part, and (first row part of a
+    // 32-k step only) the weight rows
+    auto fetch = [&](int stage, int s) {
+        const unsigned char* sa = lds + stage * STAGE;
+        const unsigned char* sw = sa + BM * TBK * 2;
+        int ks = s / MH, mh = s % MH;
+#pragma unroll
+        for (int j = 0; j < TMH; ++j)
+            fa[s & 1][j] = *(const bf16x8*)(sa + lds_off(wm * WM + (mh * TMH + j) * 16 + frow, ks * 4 + fk));
+        if (mh == 0) {
+#pragma unroll
+            for (int i = 0; i < TN; ++i) fw[ks & 1][i] = *(const bf16x8*)(sw + lds_off(wn * WN + i * 16 + frow, ks * 4 + fk));
+        }
+    };
+    // the MFMAs of sub-step s in two halves, so that the next sub-step's fragment fetch can be issued between them
+    auto mma = [&](int s, int half) {
+        constexpr int NM = TN * TMH;
+        int ks = s / MH, mh = s % MH;
+#pragma unroll
+        for (int x = 0; x < NM; ++x) {
+            if ((x < NM / 2) != (half == 0)) continue;
+            int i = x / TMH, j = x % TMH;
+            acc[i][mh * TMH + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks & 1][i], fa[s & 1][j], acc[i][mh * TMH + j], 0, 0, 0);
+        }
+    };
+#define EXE_SB __builtin_amdgcn_sched_barrier(0)
+
+    // prologue: the first ST k-tiles go to stages 0 .. ST-1; wait for the first only
+#pragma unroll
+    for (int t = 0; t < ST; ++t) issue_next(t);
     wait_cnt<LPT*(ST - 1), 15>();
     __syncthreads();
-    fetch(0, 0, 0);
+    fetch(0, 0);
     int st = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-        int nst = st + 1 == ST ? 0 : st + 1;
-        EXE_STEP(0, fetch(st, 1, 1))
-        EXE_STEP(1, fetch(st, 2, 0))
-        EXE_STEP(0, fetch(st, 3, 1))
-        // last step of the tile.  After its first half every read of this stage has been issued and has
-        // returned (lgkmcnt 0); wait for tile kt+1 as well (all but the ST-2 most recent tiles' loads),
-        // synchronise, refill the stage just vacated and fetch the first fragments of tile kt+1.
-        __builtin_amdgcn_sched_barrier(0);
-        mma(1, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        wait_cnt<LPT*(ST - 2), 0>();
-        __syncthreads();
-        issue_loads(kt + ST, st);
-        if (kt + 1 < nk) fetch(nst, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        st = nst;
-    }
-#undef EXE_STEP
-    wait_cnt<0, 15>();     // drain the tail loads before the workgroup's LDS is released
-
-    // accumulator layout: element r of lane l is (n = 8*(r/4) + 4*(l/32) + r%4, m = l%32) of its 32x32 tile
-    int S = gridDim.z;
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        int m = m0 + wm * WM + j * 32 + (lane & 31);
-        if (m >= M) continue;
+    for (int v = blockIdx.x; v < items; v += gridDim.x) {
+        int m0, n0, z;
+        locate(v, m0, n0, z);
+        int nk = k_tiles(z);
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int n = n0 + wn * WN + i * 32 + q * 8 + (lane >> 5) * 4;
-                if (n >= N) continue;
-                f32x4 v = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-                if (S > 1) *(f32x4*)(partial + ((int64_t)blockIdx.z * M + m) * N + n) = v;
-                else epilogue_store4<bf16_t>(v, m, n, N, bias, act, alpha, out_mode, out);
+            for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int kt = 0; kt < nk; ++kt) {
+            int nst = st + 1 == ST ? 0 : st + 1;
+            // every sub-step but the last: half of the MFMAs, the fetch of the following sub-step, the other half.
+            // The fragments a sub-step needs were requested half a sub-step earlier, so the wait in front of its
+            // MFMAs covers only reads that have had time to return.
+#pragma unroll
+            for (int s = 0; s < NS - 1; ++s) {
+                EXE_SB; mma(s, 0); EXE_SB;
+                fetch(st, s + 1);
+                EXE_SB; mma(s, 1); EXE_SB;
             }
+            // last sub-step of the k-tile.  After its first half every read of this stage has been issued and has
+            // returned (lgkmcnt 0); wait for the following k-tile as well (all but the ST-2 most recent
+            // k-tiles' loads), synchronise, refill the stage just vacated and fetch the first fragments of the
+            // following k-tile of this item.
+            EXE_SB; mma(NS - 1, 0); EXE_SB;
+            wait_cnt<LPT*(ST - 2), 0>();
+            __syncthreads();
+            issue_next(st);
+            if (kt + 1 < nk) fetch(nst, 0);
+            EXE_SB; mma(NS - 1, 1); EXE_SB;
+            st = nst;
+        }
+        // Epilogue; its stores drain while the next item's first k-tiles are multiplied.
+        {
+            unsigned stg = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds + ST * STAGE + wave * (EN * 128);
+            int row0 = m0 + wm * WM, col0 = n0 + wn * WN;
+            if (n_split > 1)
+                epilogue_tiles<TM, TN, EN, EPI_PARTIAL>(acc, stg, lane, row0, col0, M, N, nullptr, 1.f, partial + (int64_t)z * M * N, nullptr);
+            else if (out_mode == OUT_RESID)
+                epilogue_tiles<TM, TN, EN, EPI_RESID>(acc, stg, lane, row0, col0, M, N, bias, alpha, (float*)out, nullptr);
+            else if (out_mode == OUT_F32)
+                epilogue_tiles<TM, TN, EN, EPI_F32>(acc, stg, lane, row0, col0, M, N, bias, alpha, (float*)out, nullptr);
+            else if (act == 0)
+                epilogue_tiles<TM, TN, EN, EPI_T_RELU>(acc, stg, lane, row0, col0, M, N, bias, alpha, nullptr, (bf16_t*)out);
+            else if (act == 1)
+                epilogue_tiles<TM, TN, EN, EPI_T_GELU>(acc, stg, lane, row0, col0, M, N, bias, alpha, nullptr, (bf16_t*)out);
+            else
+                epilogue_tiles<TM, TN, EN, EPI_T>(acc, stg, lane, row0, col0, M, N, bias, alpha, nullptr, (bf16_t*)out);
+        }
+        // first fragments of the next item (not held across the epilogue: it needs the registers)
+        if (v + (int)gridDim.x < items) fetch(st, 0);
     }
+#undef EXE_SB
+    wait_cnt<0, 15>();     // drain the tail loads before the workgroup's LDS is released
 }
 
 // Sums the split-K partials in split order (deterministic) and applies the epilogue.  (A reduction fused
@@ -369,12 +541,30 @@ size_t gemm_workspace_bytes(int dtype, int M, int N, int K)
     return p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
 }
 
+// Number of persistent workgroups of a tile GEMM: one per compute unit (every configuration takes more than half
+// of a CU's LDS, so one workgroup is resident per CU), rounded down to a multiple of 8 for the XCD mapping.
+static int persistent_grid()
+{
+    static int n = 0;
+    if (!n) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+            cus = 256;
+        n = cus / 8 * 8;
+        int force = env_int("EXE_GEMM_GRID", 0);
+        if (force >= 8) n = force / 8 * 8;
+    }
+    return n;
+}
+
 template <int BM, int BN, int WM, int WN, int ST>
 static hipError_t launch_tile(const GemmArgs& a, const Plan& p, hipStream_t s)
 {
     auto kern = gemm_tile_kernel<BM, BN, WM, WN, ST>;
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
-    size_t lds = (size_t)ST * (BM + BN) * TBK * 2;
+    size_t lds = (size_t)ST * (BM + BN) * TBK * 2 + (size_t)(threads / 64) * epilogue_cols(BM, BN, WM, WN, ST) * 128;
+    static_assert(ST * (BM + BN) * TBK * 2 + (BM / WM) * (BN / WN) * epilogue_cols(BM, BN, WM, WN, ST) * 128 <= 160 * 1024, "LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -382,9 +572,10 @@ static hipError_t launch_tile(const GemmArgs& a, const Plan& p, hipStream_t s)
         attr_set = true;
     }
     int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
-    kern<<<dim3(tm * tn, 1, p.splits), threads, lds, s>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.W,
-                                                         (const bf16_t*)a.bias, a.act, a.alpha, a.out_mode, a.out,
-                                                         a.workspace, tm, tn, p.k_per_split);
+    int items = tm * tn * p.splits;
+    int grid = items < persistent_grid() ? items : persistent_grid();
+    kern<<<grid, threads, lds, s>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.W, (const bf16_t*)a.bias, a.act,
+                                    a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split, p.splits);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     int64_t quads = ((int64_t)a.M * a.N) / 4;
