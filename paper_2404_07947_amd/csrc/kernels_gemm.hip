@@ -11,6 +11,8 @@
 // consecutive output features per lane, which makes the epilogue's loads and stores 8/16-byte vectors.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -227,7 +229,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int TM = WM / 16, TN = WN / 16;       // 16x16 accumulator tiles of a wave: TM along rows, TN along features
-    constexpr int MH = TM > 4 ? TM / 4 : 1;         // row parts of the wave's tile, one per sub-step
+    constexpr int MH = TM > 2 ? TM / 2 : 1;         // row parts of the wave's tile, one per sub-step
     constexpr int TMH = TM / MH;
     constexpr int NS = 2 * MH;                      // sub-steps per k-tile
     constexpr int A_PASSES = BM / 8 / NW, B_PASSES = BN / 8 / NW;   // 1 KB wave-loads per wave per stage
@@ -263,7 +265,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         return (kend - kbeg) / TBK;
     };
 
-    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int tid = threadIdx.x, lane = tid & 63;
+    int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: keeps what derives from it in SGPRs
     int wm = wave % (BM / WM), wn = wave / (BM / WM);
 
     // ---- loader: runs ST k-tiles ahead of the MFMA loop, across item boundaries.  The source of a wave-load is a
@@ -293,18 +296,23 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         }
     };
     set_src(ld_v);
-    // issues the loader's current k-tile into `stage` and advances it; past the last item the last k-tile is
-    // loaded again, which keeps the number of loads in flight uniform
-    auto issue_next = [&](int stage) {
+    // issues wave-loads X0 .. X1-1 (A passes first, then W passes) of the loader's current k-tile into `stage`
+    auto issue_range = [&](int stage, auto x0, auto x1) {
         unsigned char* base = lds + stage * STAGE;
         const char* ka = base_a + ld_kt * (TBK * 2);
         const char* kw = base_w + ld_kt * (TBK * 2);
 #pragma unroll
-        for (int p = 0; p < A_PASSES; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ka + off_a[p]), (lds_ptr_t)(base + (p * NW + wave) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int p = 0; p < B_PASSES; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kw + off_w[p]), (lds_ptr_t)(base + BM * TBK * 2 + (p * NW + wave) * 1024), 16, 0, 0);
+        for (int x = decltype(x0)::value; x < decltype(x1)::value; ++x) {
+            if (x < A_PASSES)
+                __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ka + off_a[x]), (lds_ptr_t)(base + (x * NW + wave) * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kw + off_w[x - A_PASSES]),
+                                                 (lds_ptr_t)(base + BM * TBK * 2 + ((x - A_PASSES) * NW + wave) * 1024), 16, 0, 0);
+        }
+    };
+    // moves the loader to the next k-tile; past the last item the last k-tile is loaded again, which keeps the
+    // number of loads in flight uniform
+    auto advance = [&]() {
         if (ld_kt + 1 < ld_nk) ++ld_kt;
         else if (ld_v + (int)gridDim.x < items) {
             ld_v += gridDim.x;
@@ -312,6 +320,17 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
             set_src(ld_v);
         }
     };
+    // A k-tile's loads are issued in four parts spread over 24 MFMAs: a burst of all of them fills the queue of
+    // the CU's address unit, and a wave waiting to issue a load issues no MFMA either.
+    // (Only the MFMA-bound 256 x 256 tile does this; the smaller tiles stream weights for few rows and want every
+    // load in flight as early as possible.)
+    constexpr bool SPREAD = BM * BN >= 256 * 256;
+    constexpr int Q1 = SPREAD ? LPT / 4 : LPT, Q2 = SPREAD ? LPT / 2 : LPT, Q3 = SPREAD ? LPT * 3 / 4 : LPT;
+    using X0 = std::integral_constant<int, 0>;
+    using X1 = std::integral_constant<int, Q1>;
+    using X2 = std::integral_constant<int, Q2>;
+    using X3 = std::integral_constant<int, Q3>;
+    using X4 = std::integral_constant<int, LPT>;
 
     // MFMA operands (16x16x32): lane l holds row l%16 and the 8 k-values 8*(l/16) .. +7 of a 32-k step, i.e.
     // 16-byte chunk 4*ks + l/16 of the stage row.  The W fragments of a 32-k step are kept for all its row parts.
@@ -347,11 +366,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 
     // prologue: the first ST k-tiles go to stages 0 .. ST-1; wait for the first only
 #pragma unroll
-    for (int t = 0; t < ST; ++t) issue_next(t);
+    for (int t = 0; t < ST; ++t) {
+        issue_range(t, X0{}, X4{});
+        advance();
+    }
     wait_cnt<LPT*(ST - 1), 15>();
     __syncthreads();
     fetch(0, 0);
-    int st = 0;
+    int st = 0, fill_st = 0;
+    bool pend = false;        // parts 2 .. 4 of the k-tile going into stage fill_st are still to be issued
     for (int v = blockIdx.x; v < items; v += gridDim.x) {
         int m0, n0, z;
         locate(v, m0, n0, z);
@@ -362,23 +385,46 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
             for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int kt = 0; kt < nk; ++kt) {
             int nst = st + 1 == ST ? 0 : st + 1;
-            // every sub-step but the last: half of the MFMAs, the fetch of the following sub-step, the other half.
-            // The fragments a sub-step needs were requested half a sub-step earlier, so the wait in front of its
-            // MFMAs covers only reads that have had time to return.
+            // Every sub-step but the last: the fetch of the following sub-step's fragments, then the MFMAs (a full
+            // sub-step of MFMAs between a fetch and its use).  The first three also issue the rest of the loads
+            // whose first part went out behind the previous barrier.
+            if constexpr (NS >= 4) {
 #pragma unroll
-            for (int s = 0; s < NS - 1; ++s) {
-                EXE_SB; mma(s, 0); EXE_SB;
-                fetch(st, s + 1);
-                EXE_SB; mma(s, 1); EXE_SB;
+                for (int s = 0; s < NS - 1; ++s) {
+                    fetch(st, s + 1);
+                    if (s == 0 && pend) issue_range(fill_st, X1{}, X2{});
+                    if (s == 1 && pend) issue_range(fill_st, X2{}, X3{});
+                    if (s == 2 && pend) {
+                        issue_range(fill_st, X3{}, X4{});
+                        advance();
+                    }
+                    EXE_SB; mma(s, 0); mma(s, 1); EXE_SB;
+                }
+            } else {
+                fetch(st, 1);
+                if (pend) issue_range(fill_st, X1{}, X2{});
+                EXE_SB; mma(0, 0); EXE_SB;
+                if (pend) issue_range(fill_st, X2{}, X3{});
+                EXE_SB; mma(0, 1); EXE_SB;
+                if (pend) {
+                    issue_range(fill_st, X3{}, X4{});
+                    advance();
+                }
             }
             // last sub-step of the k-tile.  After its first half every read of this stage has been issued and has
             // returned (lgkmcnt 0); wait for the following k-tile as well (all but the ST-2 most recent
-            // k-tiles' loads), synchronise, refill the stage just vacated and fetch the first fragments of the
-            // following k-tile of this item.
+            // k-tiles' loads), synchronise, start refilling the stage just vacated and fetch the first fragments
+            // of the following k-tile of this item.
             EXE_SB; mma(NS - 1, 0); EXE_SB;
             wait_cnt<LPT*(ST - 2), 0>();
             __syncthreads();
-            issue_next(st);
+            issue_range(st, X0{}, X1{});
+            if constexpr (SPREAD) {
+                fill_st = st;
+                pend = true;
+            } else {
+                advance();
+            }
             if (kt + 1 < nk) fetch(nst, 0);
             EXE_SB; mma(NS - 1, 1); EXE_SB;
             st = nst;
