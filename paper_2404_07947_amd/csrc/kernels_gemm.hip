@@ -207,11 +207,11 @@ constexpr int epilogue_cols(int BM, int BN, int WM, int WN, int ST)
 // the global side: lane l fetches chunk (l % 8) ^ swz(row) of row l / 8.
 //
 // ST LDS stages of 64 k form a ring: while k-tile kt is multiplied, k-tiles kt+1 .. kt+ST-1 are in flight.
-// Inside a k-tile the loop is software-pipelined over sub-steps (32 k x at most 64 rows of the wave's tile): the
-// operand fragments of sub-step s+1 are fetched from LDS between the two halves of the MFMAs of sub-step s.  The
-// one barrier per k-tile sits in the middle of its last sub-step: behind it every wave has finished reading the
-// current stage and k-tile kt+1 has landed, so the loads of k-tile kt+ST are issued into the stage just vacated
-// and the first fragments of k-tile kt+1 are fetched while the last MFMAs of k-tile kt execute.
+// Inside a k-tile the loop is software-pipelined over sub-steps (32 k x 32 rows of the wave's tile): the operand
+// fragments of sub-step s+1 are fetched from LDS before the MFMAs of sub-step s are issued.  The one barrier per
+// k-tile sits in front of the MFMAs of its last sub-step: behind it every wave has finished reading the current
+// stage and k-tile kt+1 has landed, so the loads of k-tile kt+ST go into the stage just vacated and the first
+// fragments of k-tile kt+1 are fetched while the last MFMAs of k-tile kt execute.
 //
 // The MFMA is the 16x16x32 one (4 passes).  Measured on MI355X: while a SIMD executes 32x32x16 MFMAs (8 passes)
 // back to back, vector memory instructions of the waves on it are hardly issued at all (a loader wave beside an
@@ -411,11 +411,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
                     advance();
                 }
             }
-            // last sub-step of the k-tile.  After its first half every read of this stage has been issued and has
-            // returned (lgkmcnt 0); wait for the following k-tile as well (all but the ST-2 most recent
-            // k-tiles' loads), synchronise, start refilling the stage just vacated and fetch the first fragments
-            // of the following k-tile of this item.
-            EXE_SB; mma(NS - 1, 0); EXE_SB;
+            // last sub-step of the k-tile.  Its fragments were the last reads of this stage: once they have
+            // returned (lgkmcnt 0) and the following k-tile has landed (all but the ST-2 most recent k-tiles'
+            // loads), synchronise, start refilling the stage just vacated and fetch the first fragments of the
+            // following k-tile of this item behind the barrier, a full sub-step ahead of their use.
             wait_cnt<LPT*(ST - 2), 0>();
             __syncthreads();
             issue_range(st, X0{}, X1{});
@@ -426,7 +425,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
                 advance();
             }
             if (kt + 1 < nk) fetch(nst, 0);
-            EXE_SB; mma(NS - 1, 1); EXE_SB;
+            EXE_SB; mma(NS - 1, 0); mma(NS - 1, 1); EXE_SB;
             st = nst;
         }
         // Epilogue; its stores drain while the next item's first k-tiles are multiplied.
