@@ -225,7 +225,7 @@ template <int BM, int BN, int WM, int WN, int ST>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias,
     int act, float alpha, int out_mode, void* __restrict__ out, float* __restrict__ partial, int tiles_m, int tiles_n,
-    int k_per_split, int n_split)
+    int k_per_split, int n_split, int spread)
 {
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int TM = WM / 16, TN = WN / 16;       // 16x16 accumulator tiles of a wave: TM along rows, TN along features
@@ -322,10 +322,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     };
     // A k-tile's loads are issued in four parts spread over 24 MFMAs: a burst of all of them fills the queue of
     // the CU's address unit, and a wave waiting to issue a load issues no MFMA either.
-    // (Only the MFMA-bound 256 x 256 tile does this; the smaller tiles stream weights for few rows and want every
-    // load in flight as early as possible.)
-    constexpr bool SPREAD = BM * BN >= 256 * 256;
-    constexpr int Q1 = SPREAD ? LPT / 4 : LPT, Q2 = SPREAD ? LPT / 2 : LPT, Q3 = SPREAD ? LPT * 3 / 4 : LPT;
+    // (`spread` = 0 issues them all at once behind the barrier: launches that stream weights for few rows want
+    // every load in flight as early as possible.)
+    constexpr int Q1 = LPT / 4, Q2 = LPT / 2, Q3 = LPT * 3 / 4;
     using X0 = std::integral_constant<int, 0>;
     using X1 = std::integral_constant<int, Q1>;
     using X2 = std::integral_constant<int, Q2>;
@@ -418,10 +417,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
             wait_cnt<LPT*(ST - 2), 0>();
             __syncthreads();
             issue_range(st, X0{}, X1{});
-            if constexpr (SPREAD) {
+            if (spread) {
                 fill_st = st;
                 pend = true;
             } else {
+                issue_range(st, X1{}, X4{});
                 advance();
             }
             if (kt + 1 < nk) fetch(nst, 0);
@@ -521,7 +521,7 @@ enum Cfg { C64x256 = 0, C128x256, C256x256, C64x128, C128x128, C256x128, N_CFG }
 struct CfgInfo { int bm, bn; };
 static const CfgInfo CFG[N_CFG] = {{64, 256}, {128, 256}, {256, 256}, {64, 128}, {128, 128}, {256, 128}};
 
-struct Plan { int route; int cfg; int splits; int k_per_split; int tiles; };
+struct Plan { int route; int cfg; int splits; int k_per_split; int tiles; int spread; };
 
 static int env_int(const char* name, int dflt)
 {
@@ -553,7 +553,7 @@ static double plan_cost(int cfg, int splits, int M, int N, int K)
 
 static Plan make_plan(int dtype, int M, int N, int K)
 {
-    Plan p{2, 0, 1, K, 0};
+    Plan p{2, 0, 1, K, 0, 0};
     if (dtype != DT_BF16 || N % 4 != 0 || K % TBK != 0 || M < 1) return p;
     p.route = 0;
     p.cfg = C256x256;
@@ -569,10 +569,14 @@ static Plan make_plan(int dtype, int M, int N, int K)
             }
         }
     }
-    // tuning knobs (debugging / sweeps): EXE_GEMM_CFG forces a configuration, EXE_GEMM_SPLIT a split count
+    // tuning knobs (debugging / sweeps): EXE_GEMM_CFG forces a configuration, EXE_GEMM_SPLIT a split
+    // count, EXE_GEMM_SPREAD the load issue pattern
     int force_cfg = env_int("EXE_GEMM_CFG", -1), force_split = env_int("EXE_GEMM_SPLIT", 0);
     if (force_cfg >= 0 && force_cfg < N_CFG) p.cfg = force_cfg;
     if (force_split > 0 && (K / TBK) % force_split == 0) p.splits = force_split;
+    p.spread = p.cfg == C256x256;
+    int force_spread = env_int("EXE_GEMM_SPREAD", -1);
+    if (force_spread >= 0) p.spread = force_spread != 0;
     p.tiles = ((M + CFG[p.cfg].bm - 1) / CFG[p.cfg].bm) * ((N + CFG[p.cfg].bn - 1) / CFG[p.cfg].bn);
     p.k_per_split = K / p.splits;
     return p;
@@ -620,7 +624,7 @@ static hipError_t launch_tile(const GemmArgs& a, const Plan& p, hipStream_t s)
     int items = tm * tn * p.splits;
     int grid = items < persistent_grid() ? items : persistent_grid();
     kern<<<grid, threads, lds, s>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.W, (const bf16_t*)a.bias, a.act,
-                                    a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split, p.splits);
+                                    a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split, p.splits, p.spread);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     int64_t quads = ((int64_t)a.M * a.N) / 4;
