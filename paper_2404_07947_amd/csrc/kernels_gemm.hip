@@ -296,18 +296,27 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         }
     };
     set_src(ld_v);
-    // issues wave-loads X0 .. X1-1 (A passes first, then W passes) of the loader's current k-tile into `stage`
+    // issues wave-loads X0 .. X1-1 (A passes first, then W passes) of the loader's current k-tile into `stage`.
+    // The load is written as inline assembly on purpose: the compiler assumes that any later DS read may alias
+    // the destination of a direct-to-LDS load it knows of, and puts a vmcnt(0) in front of the fragment reads,
+    // which empties the ring of stages at every k-tile.  Completion is tracked by the explicit waits below.
+    unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+    // (m0, the LDS destination, is a reserved register: naming it as clobbered draws a warning, but keeps the
+    // compiler from merging its own m0 set-ups across the statement)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+    auto load_to_lds = [&](const char* src, unsigned voff, unsigned dst) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(src) : "memory", "m0");
+    };
+#pragma clang diagnostic pop
     auto issue_range = [&](int stage, auto x0, auto x1) {
-        unsigned char* base = lds + stage * STAGE;
+        unsigned base = lds_base + stage * STAGE + wave * 1024;
         const char* ka = base_a + ld_kt * (TBK * 2);
         const char* kw = base_w + ld_kt * (TBK * 2);
 #pragma unroll
         for (int x = decltype(x0)::value; x < decltype(x1)::value; ++x) {
-            if (x < A_PASSES)
-                __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ka + off_a[x]), (lds_ptr_t)(base + (x * NW + wave) * 1024), 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kw + off_w[x - A_PASSES]),
-                                                 (lds_ptr_t)(base + BM * TBK * 2 + ((x - A_PASSES) * NW + wave) * 1024), 16, 0, 0);
+            if (x < A_PASSES) load_to_lds(ka, off_a[x], base + x * NW * 1024);
+            else load_to_lds(kw, off_w[x - A_PASSES], base + BM * TBK * 2 + (x - A_PASSES) * NW * 1024);
         }
     };
     // moves the loader to the next k-tile; past the last item the last k-tile is loaded again, which keeps the
