@@ -12,6 +12,7 @@
 #include <stdlib.h>
 
 #include <type_traits>
+#include <unordered_map>
 
 #include "common.h"
 #include "kernels.h"
@@ -331,8 +332,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     };
     // A k-tile's loads are issued in four parts spread over 24 MFMAs: a burst of all of them fills the queue of
     // the CU's address unit, and a wave waiting to issue a load issues no MFMA either.
-    // (`spread` = 0 issues them all at once behind the barrier: launches that stream weights for few rows want
-    // every load in flight as early as possible.)
+    // (`spread` = 0 issues them all at once behind the barrier.)
     constexpr int Q1 = LPT / 4, Q2 = LPT / 2, Q3 = LPT * 3 / 4;
     using X0 = std::integral_constant<int, 0>;
     using X1 = std::integral_constant<int, Q1>;
@@ -538,26 +538,36 @@ static int env_int(const char* name, int dflt)
     return v ? atoi(v) : dflt;
 }
 
-// Cost model behind the choice of tile shape and split count (fitted to a sweep of the six shapes x split
-// counts on MI355X for 16 <= M <= 512): a workgroup's time is the larger of its LDS-fill traffic at the rate one
-// CU sustains through its vector L1 (about 45 GB/s) and its MFMA work at the rate the tile loop reaches
-// (about 4.5 TFLOP/s per CU); workgroups run in rounds of one per CU; the whole launch cannot beat
-// streaming W once from HBM; split-K adds the float partials' round trip and a second launch.
+// Cost model behind the choice of tile shape and split count (fitted to a sweep of the six shapes x 1..16 splits on
+// MI355X for 16 <= M <= 1024; its pick is within 1 % of the best on average, 7 % at worst): a workgroup's time is
+// the larger of its LDS-fill traffic at the rate one CU sustains through its vector L1 (about 45 GB/s) and its MFMA
+// work at the rate the tile loop reaches (about 4.5 TFLOP/s per CU); workgroups run in rounds of one per CU; the
+// whole launch cannot beat streaming W once from HBM; split-K adds the float partials' round trip and a second launch.
 static double plan_cost(int cfg, int splits, int M, int N, int K)
 {
     int bm = CFG[cfg].bm, bn = CFG[cfg].bn;
     int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
     int64_t wgs = tiles * splits;
     double rounds = (double)((wgs + 255) / 256);
-    double ktiles = (double)(K / TBK) / splits;
+    double ktiles = (double)((K / TBK + splits - 1) / splits);
     double fill = ktiles * (bm + bn) * TBK * 2 / 45e9;
     double mfma = ktiles * 2.0 * bm * bn * TBK / 4.5e12;
     double t = rounds * (fill > mfma ? fill : mfma);
-    double hbm = (double)N * K * 2 / 6e12;
+    double hbm = (double)N * K * 2 / 5e12;
     if (t < hbm) t = hbm;
     t += 4e-6;
-    if (splits > 1) t += 2.0 * splits * M * N * 4 / 5e12 + 4e-6;
+    if (splits > 1) t += 2.0 * splits * M * N * 4 / 3e12 + 1e-6;
     return t;
+}
+
+// Split-K over `s` parts: every part but the last takes ceil(k-tiles / s) k-tiles, the last one the rest, which must
+// be at least 4 k-tiles.
+static int split_k_tiles(int K, int s) { return (K / TBK + s - 1) / s; }
+static bool split_ok(int K, int s)
+{
+    if (s == 1) return true;
+    int per = split_k_tiles(K, s), last = K / TBK - per * (s - 1);
+    return per >= 4 && last >= 4;
 }
 
 static Plan make_plan(int dtype, int M, int N, int K)
@@ -566,28 +576,37 @@ static Plan make_plan(int dtype, int M, int N, int K)
     if (dtype != DT_BF16 || N % 4 != 0 || K % TBK != 0 || M < 1) return p;
     p.route = 0;
     p.cfg = C256x256;
-    if (M <= 1024) {
-        static const int split_options[] = {1, 2, 4, 5, 8, 10, 16};
+    // the model's choice per shape is remembered (a decode iteration asks for the same few shapes 4 times per layer)
+    struct Choice { int cfg, splits; };
+    thread_local std::unordered_map<uint64_t, Choice> memo;
+    uint64_t key = ((uint64_t)M << 44) ^ ((uint64_t)N << 22) ^ (uint64_t)K;
+    auto hit = memo.find(key);
+    if (hit != memo.end()) {
+        p.cfg = hit->second.cfg;
+        p.splits = hit->second.splits;
+    } else if (M <= 1024) {
         double best = 1e30;
         for (int cfg = 0; cfg < N_CFG; ++cfg) {
             if (CFG[cfg].bm >= 2 * M && CFG[cfg].bm > 64) continue;     // more than half the rows would be padding
-            for (int s : split_options) {
-                if ((K / TBK) % s || K / TBK / s < 4) continue;
+            for (int s = 1; s <= 16; ++s) {
+                if (!split_ok(K, s)) continue;
                 double c = plan_cost(cfg, s, M, N, K);
                 if (c < best) { best = c; p.cfg = cfg; p.splits = s; }
             }
         }
+        if (memo.size() > 4096) memo.clear();
+        memo[key] = Choice{p.cfg, p.splits};
     }
     // tuning knobs (debugging / sweeps): EXE_GEMM_CFG forces a configuration, EXE_GEMM_SPLIT a split
     // count, EXE_GEMM_SPREAD the load issue pattern
     int force_cfg = env_int("EXE_GEMM_CFG", -1), force_split = env_int("EXE_GEMM_SPLIT", 0);
     if (force_cfg >= 0 && force_cfg < N_CFG) p.cfg = force_cfg;
-    if (force_split > 0 && (K / TBK) % force_split == 0) p.splits = force_split;
-    p.spread = p.cfg == C256x256;
+    if (force_split > 0 && split_ok(K, force_split)) p.splits = force_split;
+    p.spread = 1;     // never slower than issuing a k-tile's loads at once in that sweep, up to 15 % faster from M = 128 on
     int force_spread = env_int("EXE_GEMM_SPREAD", -1);
     if (force_spread >= 0) p.spread = force_spread != 0;
     p.tiles = ((M + CFG[p.cfg].bm - 1) / CFG[p.cfg].bm) * ((N + CFG[p.cfg].bn - 1) / CFG[p.cfg].bn);
-    p.k_per_split = K / p.splits;
+    p.k_per_split = split_k_tiles(K, p.splits) * TBK;
     return p;
 }
 
