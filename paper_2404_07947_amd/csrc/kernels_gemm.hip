@@ -530,7 +530,7 @@ enum Cfg { C64x256 = 0, C128x256, C256x256, C64x128, C128x128, C256x128, N_CFG }
 struct CfgInfo { int bm, bn; };
 static const CfgInfo CFG[N_CFG] = {{64, 256}, {128, 256}, {256, 256}, {64, 128}, {128, 128}, {256, 128}};
 
-struct Plan { int route; int cfg; int splits; int k_per_split; int tiles; int spread; };
+struct Plan { int route; int cfg; int splits; int k_per_split; int tiles; int spread; double cost; };
 
 static int env_int(const char* name, int dflt)
 {
@@ -572,19 +572,22 @@ static bool split_ok(int K, int s)
 
 static Plan make_plan(int dtype, int M, int N, int K)
 {
-    Plan p{2, 0, 1, K, 0, 0};
+    Plan p{2, 0, 1, K, 0, 0, 0.0};
     if (dtype != DT_BF16 || N % 4 != 0 || K % TBK != 0 || M < 1) return p;
     p.route = 0;
     p.cfg = C256x256;
     // the model's choice per shape is remembered (a decode iteration asks for the same few shapes 4 times per layer)
-    struct Choice { int cfg, splits; };
+    struct Choice { int cfg, splits; double cost; };
     thread_local std::unordered_map<uint64_t, Choice> memo;
     uint64_t key = ((uint64_t)M << 44) ^ ((uint64_t)N << 22) ^ (uint64_t)K;
     auto hit = memo.find(key);
     if (hit != memo.end()) {
         p.cfg = hit->second.cfg;
         p.splits = hit->second.splits;
-    } else if (M <= 1024) {
+        p.cost = hit->second.cost;
+    } else if (M > 1024) {
+        p.cost = plan_cost(C256x256, 1, M, N, K);
+    } else {
         double best = 1e30;
         for (int cfg = 0; cfg < N_CFG; ++cfg) {
             if (CFG[cfg].bm >= 2 * M && CFG[cfg].bm > 64) continue;     // more than half the rows would be padding
@@ -594,8 +597,9 @@ static Plan make_plan(int dtype, int M, int N, int K)
                 if (c < best) { best = c; p.cfg = cfg; p.splits = s; }
             }
         }
+        p.cost = best;
         if (memo.size() > 4096) memo.clear();
-        memo[key] = Choice{p.cfg, p.splits};
+        memo[key] = Choice{p.cfg, p.splits, p.cost};
     }
     // tuning knobs (debugging / sweeps): EXE_GEMM_CFG forces a configuration, EXE_GEMM_SPLIT a split
     // count, EXE_GEMM_SPREAD the load issue pattern
@@ -612,12 +616,6 @@ static Plan make_plan(int dtype, int M, int N, int K)
 
 int gemm_route(int dtype, int M, int N, int K) { return make_plan(dtype, M, N, K).route; }
 
-size_t gemm_workspace_bytes(int dtype, int M, int N, int K)
-{
-    Plan p = make_plan(dtype, M, N, K);
-    return p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
-}
-
 // Number of persistent workgroups of a tile GEMM: one per compute unit (every configuration takes more than half
 // of a CU's LDS, so one workgroup is resident per CU), rounded down to a multiple of 8 for the XCD mapping.
 static int persistent_grid()
@@ -633,6 +631,32 @@ static int persistent_grid()
         if (force >= 8) n = force / 8 * 8;
     }
     return n;
+}
+
+// A launch of many 256 x 256 tiles runs in rounds of one tile per CU, and a last round that fills few CUs costs as
+// much as a full one.  split_rows returns the number of leading rows whose tiles fill whole rounds when handing the
+// remaining rows (a few hundred) to a second, separately planned launch is cheaper by the cost model, else M.
+static int split_rows(int dtype, int M, int N, int K)
+{
+    if (M <= 1024 || make_plan(dtype, M, N, K).route != 0) return M;
+    int G = persistent_grid();
+    int tn = (N + 255) / 256, tm = (M + 255) / 256, total = tm * tn;
+    int rounds = total / G;
+    if (rounds < 1 || total == rounds * G) return M;
+    int tm1 = rounds * G / tn;
+    if (tm1 < 1 || tm1 >= tm) return M;
+    int M1 = tm1 * 256;
+    double whole = plan_cost(C256x256, 1, M, N, K);
+    double parts = plan_cost(C256x256, 1, M1, N, K) + make_plan(dtype, M - M1, N, K).cost;
+    return parts < whole ? M1 : M;
+}
+
+size_t gemm_workspace_bytes(int dtype, int M, int N, int K)
+{
+    int M1 = split_rows(dtype, M, N, K);
+    if (M1 < M) return gemm_workspace_bytes(dtype, M - M1, N, K);
+    Plan p = make_plan(dtype, M, N, K);
+    return p.splits > 1 ? (size_t)p.splits * M * N * sizeof(float) : 0;
 }
 
 template <int BM, int BN, int WM, int WN, int ST>
@@ -664,6 +688,17 @@ static hipError_t launch_tile(const GemmArgs& a, const Plan& p, hipStream_t s)
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    int M1 = split_rows(a.dtype, a.M, a.N, a.K);
+    if (M1 < a.M) {
+        GemmArgs head = a, tail = a;
+        head.M = M1;
+        tail.M = a.M - M1;
+        size_t esz = a.dtype == DT_BF16 ? 2 : 4, osz = a.out_mode == OUT_T ? esz : 4;
+        tail.A = (const char*)a.A + (size_t)M1 * a.K * esz;
+        tail.out = (char*)a.out + (size_t)M1 * a.N * osz;
+        hipError_t e = launch_gemm(head, s);
+        return e != hipSuccess ? e : launch_gemm(tail, s);
+    }
     Plan p = make_plan(a.dtype, a.M, a.N, a.K);
     if (p.splits > 1 && (!a.workspace || a.workspace_bytes < gemm_workspace_bytes(a.dtype, a.M, a.N, a.K)))
         return hipErrorInvalidValue;

@@ -28,11 +28,12 @@ def rnd(shape, seed, scale=1.0, dtype=torch.bfloat16):
 
 # ------------------------------------------------------------------ GEMM
 # (M, N, K): the shapes cover every tile configuration (64/128/256 rows x 128/256 columns), with and without
-# split-K, ragged M and N edges, and the generic kernel.
+# split-K, ragged M and N edges, a launch split into whole rounds and a remainder, and the generic kernel.
 GEMM_CASES = [
     (1, 512, 512), (16, 5120, 5120), (17, 1024, 2560), (33, 2048, 512), (64, 15360, 5120), (50, 50272, 512),
     (65, 512, 1024), (200, 1024, 512), (300, 640, 2048), (1000, 2048, 512),
     (4099, 3072, 256), (2049, 6144, 128),
+    (2100, 8192, 2048),      # 9 x 32 tiles of 256 x 256: one whole round plus a 52-row remainder launch
     (100, 15360, 1024), (200, 8192, 512), (256, 5120, 5120), (128, 5120, 2048), (64, 8192, 256),
     (16, 512, 64), (70, 768, 128), (250, 8448, 192), (130, 260, 64),
     (37, 100, 72), (5, 52, 8),
@@ -42,7 +43,7 @@ GEMM_CASES = [
 @pytest.mark.parametrize("M,N,K", GEMM_CASES)
 @pytest.mark.parametrize("mode", ["act_relu", "act_gelu", "resid", "f32"])
 def test_gemm_bf16(M, N, K, mode):
-    if mode != "act_relu" and (M, N, K) in [(64, 15360, 5120), (50, 50272, 512), (4099, 3072, 256)]:
+    if mode != "act_relu" and (M, N, K) in [(64, 15360, 5120), (50, 50272, 512), (4099, 3072, 256), (2100, 8192, 2048)]:
         pytest.skip("large shapes run once")
     print(f"gemm bf16 M={M} N={N} K={K} mode={mode} route={exe.lib().exe_op_gemm_workspace(BF16, M, N, K)}", flush=True)
     A = rnd((M, K), 1, 1.0)
@@ -51,7 +52,8 @@ def test_gemm_bf16(M, N, K, mode):
     Ad, Wd, bd = A.to(DEV), W.to(DEV), b.to(DEV)
     ws_bytes = exe.exe_op_gemm_workspace(BF16, M, N, K)
     ws = torch.zeros(max(ws_bytes // 4, 1), dtype=torch.float32, device=DEV)
-    rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(M).integers(0, M, 6)]))
+    rows = np.unique(np.concatenate([[0, M - 1, min(M - 1, 2047), min(M - 1, 2048)],
+                                     np.random.default_rng(M).integers(0, M, 6)]))
     ref = prim().linear(A.float().numpy()[rows], W.float().numpy(), b.float().numpy())
     alpha = 1.0
     if mode == "act_relu" or mode == "act_gelu":
