@@ -27,7 +27,8 @@ Readings where the paper leaves the timeline open (the same ones the library doc
   * a query of output length s is encoded once, spends ceil(s / N_D) - 1 whole cycles and then
     1 + ((s - 1) mod N_D) iterations of its last decoding phase;
   * table look-ups interpolate bilinearly in (batch, length) between profiled points, clamp the length to the
-    profiled range and scale in proportion to the batch beyond the largest profiled batch.
+    profiled range and scale in proportion to the batch outside the profiled batches (an expected batch of half a
+    query costs half a one-query step: the step then runs every other cycle).
 """
 from __future__ import annotations
 
@@ -73,7 +74,9 @@ class Table:
         if b > self.batches[-1]:
             scale = b / self.batches[-1]
             b = float(self.batches[-1])
-        b = max(b, float(self.batches[0]))
+        if b < self.batches[0]:
+            scale = b / self.batches[0]
+            b = float(self.batches[0])
         l = min(max(length, float(self.lengths[0])), float(self.lengths[-1]))
 
         def bracket(grid, x):

@@ -15,6 +15,8 @@ DECLARED_SYMBOLS = [
     "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_profile", "exe_run_rra", "exe_kernel_timing",
     "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_norm", "exe_op_prefill_attention",
     "exe_op_decode_attention", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
+    # exe_sched.h (host only)
+    "exe_sim_completion", "exe_sim_step_ms", "exe_sim_rra", "exe_sim_waa", "exe_sched_search", "exe_sched_rra",
 ]
 KERNEL_KINDS = ["gemm_tile", "gemm_skinny", "prefill_attn", "decode_attn", "cross_attn", "norm", "other"]
 
@@ -42,6 +44,34 @@ class ProfileRow(C.Structure):
     _fields_ = [("phase", C.c_int32), ("batch", C.c_int32), ("length", C.c_int32), ("ragged", C.c_int32),
                 ("total_tokens", C.c_int32), ("attn_ms_per_layer", C.c_float), ("rest_ms_per_layer", C.c_float),
                 ("head_ms", C.c_float), ("full_step_ms", C.c_float), ("std_ms", C.c_float), ("n_timed", C.c_int32)]
+
+
+class SimTable(C.Structure):
+    _fields_ = [("rows", C.POINTER(ProfileRow)), ("n_rows", C.c_int32), ("n_layers_encode", C.c_int32),
+                ("n_layers_decode", C.c_int32)]
+
+
+class SimRraResult(C.Structure):
+    _fields_ = [(n, C.c_double) for n in
+                ("b_e", "b_d", "completed_fraction", "context_length", "encode_ms", "decode_ms", "cycle_ms",
+                 "tokens_per_cycle", "throughput_tok_s", "throughput_seq_s", "latency_ms", "occupancy_exact")]
+
+
+class SimWaaResult(C.Structure):
+    _fields_ = [("b_e", C.c_double), ("b_d", C.c_double), ("encode_ms", C.c_double), ("decode_ms", C.c_double),
+                ("gpus_encode", C.c_int32), ("gpus_decode", C.c_int32), ("throughput_seq_s", C.c_double)]
+
+
+class SchedResult(C.Structure):
+    _fields_ = [("found", C.c_int32), ("x1", C.c_int32), ("x2", C.c_int32), ("throughput", C.c_double),
+                ("latency", C.c_double), ("evaluations", C.c_int32), ("blocks", C.c_int32)]
+
+
+class SchedRraResult(C.Structure):
+    _fields_ = [("search", SchedResult), ("decode_batch", C.c_int32), ("n_decode", C.c_int32), ("sim", SimRraResult)]
+
+
+PERF_FN = C.CFUNCTYPE(C.c_int, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double))
 
 
 class LengthDist(C.Structure):
@@ -103,6 +133,14 @@ def lib():
     L.exe_rel_bucket.argtypes = [i32, i32, i32, i32]
     L.exe_last_error.restype = C.c_char_p
     L.exe_version.restype = C.c_char_p
+    dp, f64 = C.POINTER(C.c_double), C.c_double
+    L.exe_sim_completion.argtypes = [dp, i32, i32, dp, dp]
+    L.exe_sim_step_ms.argtypes = [C.POINTER(SimTable), i32, f64, f64, dp]
+    L.exe_sim_rra.argtypes = [C.POINTER(SimTable), dp, i32, dp, i32, f64, i32, i32, C.POINTER(SimRraResult)]
+    L.exe_sim_waa.argtypes = [C.POINTER(SimTable), dp, i32, dp, i32, f64, i32, C.POINTER(SimWaaResult)]
+    L.exe_sched_search.argtypes = [PERF_FN, vp, i32, i32, i32, i32, f64, f64, f64, C.POINTER(SchedResult)]
+    L.exe_sched_rra.argtypes = [C.POINTER(SimTable), dp, i32, dp, i32, i32, i32, i32, i32, i32, f64, f64, f64,
+                                C.POINTER(SchedRraResult)]
     _lib = L
     return L
 
@@ -275,3 +313,87 @@ def exe_op_decode_attention(dtype, B, q, q_stride, kv, k_offset, cap, length, qp
 
 def exe_op_argmax(logits, rows, n, out, stream=None):
     _check(lib().exe_op_argmax(_stream_ptr(stream), _dev(logits), rows, n, _dev(out)))
+
+
+# ---- schedule simulator and scheduling search (exe_sched.h; host only, no GPU needed) ----
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _dp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def _as_dict(st):
+    out = {}
+    for f, _ in st._fields_:
+        v = getattr(st, f)
+        out[f] = _as_dict(v) if isinstance(v, C.Structure) else v
+    return out
+
+
+def make_sim_table(rows: Sequence[dict], n_layers_encode: int, n_layers_decode: int):
+    """rows: dicts as Model.profile returns them (phase, batch, length, attn_ms_per_layer, rest_ms_per_layer, head_ms
+    are read).  Returns an object to pass as `table`; it owns the row storage."""
+    arr = (ProfileRow * len(rows))()
+    for i, r in enumerate(rows):
+        for f, _ in ProfileRow._fields_:
+            if f in r:
+                setattr(arr[i], f, r[f])
+    t = SimTable(arr, len(rows), n_layers_encode, n_layers_decode)
+    t._keep = arr
+    return t
+
+
+def exe_sim_completion(p_out, n_decode: int):
+    p = _f64(p_out)
+    pu = np.zeros(n_decode, dtype=np.float64)
+    frac = C.c_double()
+    _check(lib().exe_sim_completion(_dp(p), len(p), n_decode, _dp(pu), C.byref(frac)))
+    return pu, frac.value
+
+
+def exe_sim_step_ms(table, phase: int, batch: float, length: float) -> float:
+    ms = C.c_double()
+    _check(lib().exe_sim_step_ms(C.byref(table), phase, batch, length, C.byref(ms)))
+    return ms.value
+
+
+def exe_sim_rra(table, p_in, p_out, decode_batch: float, n_decode: int, latency_len: int) -> dict:
+    pi, po = _f64(p_in), _f64(p_out)
+    r = SimRraResult()
+    _check(lib().exe_sim_rra(C.byref(table), _dp(pi), len(pi), _dp(po), len(po), decode_batch, n_decode, latency_len,
+                             C.byref(r)))
+    return _as_dict(r)
+
+
+def exe_sim_waa(table, p_in, p_out, encode_batch: float, n_gpus: int) -> dict:
+    pi, po = _f64(p_in), _f64(p_out)
+    r = SimWaaResult()
+    _check(lib().exe_sim_waa(C.byref(table), _dp(pi), len(pi), _dp(po), len(po), encode_batch, n_gpus, C.byref(r)))
+    return _as_dict(r)
+
+
+def exe_sched_search(perf, r1, r2, eps_throughput: float, eps_latency: float, latency_bound: float) -> dict:
+    """perf(x1, x2) -> (latency, throughput)."""
+    def cb(x1, x2, user, lat, thr):
+        try:
+            lat[0], thr[0] = perf(x1, x2)
+            return 0
+        except Exception:                                  # reported by the library as a failed evaluation
+            return 1
+    r = SchedResult()
+    _check(lib().exe_sched_search(PERF_FN(cb), None, r1[0], r1[1], r2[0], r2[1], eps_throughput, eps_latency,
+                                  latency_bound, C.byref(r)))
+    return _as_dict(r)
+
+
+def exe_sched_rra(table, p_in, p_out, bd_range, nd_range, latency_len: int, latency_bound_ms: float,
+                  eps_throughput: float = 0.0, eps_latency_ms: float = 0.0) -> dict:
+    pi, po = _f64(p_in), _f64(p_out)
+    r = SchedRraResult()
+    _check(lib().exe_sched_rra(C.byref(table), _dp(pi), len(pi), _dp(po), len(po), bd_range[0], bd_range[1],
+                               nd_range[0], nd_range[1], latency_len, latency_bound_ms, eps_throughput,
+                               eps_latency_ms, C.byref(r)))
+    return _as_dict(r)

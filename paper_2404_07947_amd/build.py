@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libexe.so")
-SOURCES = ["kernels_elementwise.hip", "kernels_gemm.hip", "kernels_attn.hip", "runtime.hip"]
+SOURCES = ["kernels_elementwise.hip", "kernels_gemm.hip", "kernels_attn.hip", "runtime.hip", "sched.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -28,7 +28,7 @@ def build(force: bool = False, verbose: bool = True) -> str:
 
     def compile_one(src: str) -> str:
         s = os.path.join(CSRC, src)
-        o = os.path.join(OBJ, src.replace(".hip", ".o"))
+        o = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
         if not force and os.path.exists(o) and os.path.getmtime(o) >= max(os.path.getmtime(s), hm):
             return o
         cmd = [HIPCC, *FLAGS, "-c", s, "-o", o]

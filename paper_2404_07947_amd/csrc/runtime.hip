@@ -35,6 +35,14 @@ static int fail(int code, const char* fmt, ...)
     } while (0)
 
 extern "C" const char* exe_last_error(void) { return g_err; }
+namespace exe {
+// for the library's other translation units: records the message exe_last_error() returns, passes the code through
+int set_error(int code, const char* msg)
+{
+    snprintf(g_err, sizeof(g_err), "%s", msg);
+    return code;
+}
+}  // namespace exe
 extern "C" const char* exe_version(void) { return "exe 0.1 (gfx950)"; }
 
 // ---------------------------------------------------------------- T5 relative-position buckets (exact)

@@ -107,6 +107,7 @@ def test_table_lookup():
     assert t.time_ms(10, 10) == pytest.approx(3 + (9 - 3) * 0.5)
     assert t.time_ms(32, 20) == pytest.approx(40.0)                                   # beyond the grid: proportional
     assert t.time_ms(4, 5) == t.time_ms(4, 10) and t.time_ms(4, 99) == t.time_ms(4, 20)  # length clamped
+    assert t.time_ms(0.5, 10) == pytest.approx(0.5)                                   # below the grid: proportional
     assert t.time_ms(0, 10) == 0.0
 
 
