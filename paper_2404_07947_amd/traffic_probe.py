@@ -38,10 +38,12 @@ def main():
         W = (torch.randn((N, K), device=DEV) * 0.02).to(torch.bfloat16)
         b = torch.randn((N,), device=DEV).to(torch.bfloat16)
         out = torch.empty((T, N), dtype=torch.bfloat16, device=DEV)
-        exe.exe_op_gemm(1, T, N, K, A, W, b, 0, 1.0, 0, out, None)
+        # (the rows beyond whole rounds of tiles go to a second launch, which may use split-K partials)
+        ws = torch.empty(max(exe.exe_op_gemm_workspace(1, T, N, K) // 4, 1), dtype=torch.float32, device=DEV)
+        exe.exe_op_gemm(1, T, N, K, A, W, b, 0, 1.0, 0, out, ws)
         torch.cuda.synchronize()
         print(f"gemm {name} M={T} N={N} K={K}: reads {(T * K + N * K) * 2} bytes, writes {T * N * 2} bytes")
-        del A, W, b, out
+        del A, W, b, out, ws
 
     # 3. decode attention at batch 256 with the bench job's K/V lengths after 64 decode steps
     job = wl.workload_opt13b(256)
