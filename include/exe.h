@@ -132,6 +132,28 @@ int exe_seq_release(exe_model_t* m, int32_t n, const int32_t* seq_ids);
  * or a negative status. */
 int exe_seq_length(exe_model_t* m, int32_t seq_id);
 
+/*
+ * K/V hand-over (Section 3 "XRunner": for WAA scheduling the key/value cache entries of a query move from the
+ * encoding GPU to the decoding GPU through CPU memory).  exe_seq_export copies a live sequence's entries, without
+ * the unused capacity of its extent, into a host buffer: self-attention entries
+ * [decoder layer][K|V][head][kv_len][head_dim] in the storage type, then (encoder-decoder models) the cross-attention
+ * entries [decoder layer][K|V][head][cross_len][head_dim]; the sequence stays live (release it separately).
+ * exe_seq_import admits those entries under a free sequence id of a model of the same shape and type (this or
+ * another one, on any GPU), with capacity for reserve_length positions (<= 0: kv_len + 256; clamped to the position
+ * table), after which exe_decode_step continues the sequence from the token the caller kept.
+ * host_buf: host memory (pinned memory makes the copy faster), buf_bytes >= exe_seq_export_bytes; both calls
+ * synchronise the model's stream.  Errors: EXE_ERR_BAD_SEQ (id not live / already live), EXE_ERR_ARG (buffer too
+ * small), EXE_ERR_BAD_LENGTH (state inconsistent with the model), EXE_ERR_OOM_KV (pool full; nothing is admitted).
+ */
+typedef struct exe_seq_state {
+    int32_t kv_len;                /* self-attention positions memoized */
+    int32_t cross_len;             /* encoder length of an encoder-decoder sequence, else 0 */
+} exe_seq_state_t;
+int64_t exe_seq_export_bytes(exe_model_t* m, int32_t seq_id);       /* bytes, or a negative status */
+int exe_seq_export(exe_model_t* m, int32_t seq_id, void* host_buf, uint64_t buf_bytes, exe_seq_state_t* state);
+int exe_seq_import(exe_model_t* m, int32_t seq_id, const void* host_buf, uint64_t buf_bytes,
+                   const exe_seq_state_t* state, int32_t reserve_length);
+
 /* Pool accounting (bytes). Any pointer may be NULL. */
 int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used_bytes, uint64_t* largest_free_bytes,
                  int32_t* live_seqs);

@@ -12,7 +12,7 @@ _lib = None
 
 DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
-    "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_profile", "exe_run_rra", "exe_kernel_timing",
+    "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_profile", "exe_run_rra", "exe_kernel_timing",
     "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_norm", "exe_op_prefill_attention",
     "exe_op_decode_attention", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
     # exe_sched.h (host only)
@@ -74,6 +74,10 @@ class SchedRraResult(C.Structure):
 PERF_FN = C.CFUNCTYPE(C.c_int, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double))
 
 
+class SeqState(C.Structure):
+    _fields_ = [("kv_len", C.c_int32), ("cross_len", C.c_int32)]
+
+
 class LengthDist(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mean", C.c_float), ("std", C.c_float), ("lo", C.c_int32),
                 ("hi", C.c_int32), ("seed", C.c_uint64)]
@@ -119,6 +123,10 @@ def lib():
     L.exe_seq_release.argtypes = [vp, i32, ip]
     L.exe_seq_length.argtypes = [vp, i32]
     L.exe_kv_stats.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), ip]
+    L.exe_seq_export_bytes.argtypes = [vp, i32]
+    L.exe_seq_export_bytes.restype = C.c_int64
+    L.exe_seq_export.argtypes = [vp, i32, vp, C.c_uint64, C.POINTER(SeqState)]
+    L.exe_seq_import.argtypes = [vp, i32, vp, C.c_uint64, C.POINTER(SeqState), i32]
     L.exe_profile.argtypes = [vp, i32, ip, i32, ip, i32, C.POINTER(LengthDist), i32, C.POINTER(ProfileRow), i32, ip]
     L.exe_run_rra.argtypes = [vp, C.POINTER(RraConfig), i32, ip, ip, ip, ip, C.POINTER(RraStats)]
     L.exe_kernel_timing.argtypes = [vp, i32]
@@ -259,6 +267,21 @@ class Model:
         _check(lib().exe_profile(self._h, phase, _ip(bs), len(bs), _ip(ls), len(ls),
                                  C.byref(dist) if dist is not None else None, n_steps, rows, cap, C.byref(n)))
         return [{f: getattr(rows[i], f) for f, _ in ProfileRow._fields_} for i in range(n.value)]
+
+    def seq_export(self, seq_id: int):
+        """Returns (host buffer as a numpy uint8 array, state dict) of a live sequence's K/V entries."""
+        n = int(lib().exe_seq_export_bytes(self._h, seq_id))
+        if n < 0:
+            _check(n)
+        buf = np.empty(max(n, 1), dtype=np.uint8)
+        st = SeqState()
+        _check(lib().exe_seq_export(self._h, seq_id, buf.ctypes.data_as(C.c_void_p), n, C.byref(st)))
+        return buf[:n], {"kv_len": st.kv_len, "cross_len": st.cross_len}
+
+    def seq_import(self, seq_id: int, buf, state: dict, reserve_length: int = 0) -> None:
+        buf = np.ascontiguousarray(buf, dtype=np.uint8)
+        st = SeqState(state["kv_len"], state["cross_len"])
+        _check(lib().exe_seq_import(self._h, seq_id, buf.ctypes.data_as(C.c_void_p), buf.nbytes, C.byref(st), reserve_length))
 
     def run_rra(self, decode_batch: int, n_decode: int, input_lengths, output_lengths, tokens_packed,
                 max_encode_batch: int = 32, adjust: bool = False, workload_tolerance: float = 0.25):

@@ -897,6 +897,100 @@ extern "C" int exe_seq_length(exe_model_t* m, int32_t seq_id)
     return m->seqs[seq_id].len;
 }
 
+// ---------------------------------------------------------------- K/V hand-over (Section 3 "XRunner", WAA scheduling)
+// Exported layout: the self-attention entries [decoder layer][K|V][head][kv_len][head_dim] in the storage type,
+// then (encoder-decoder models) the cross-attention entries [decoder layer][K|V][head][cross_len][head_dim]:
+// the extent without its unused capacity.  Either side of the copy is one strided 2-D transfer.
+static uint64_t export_bytes_of(const exe_model* m, const Seq& s)
+{
+    uint64_t rows = (uint64_t)n_dec_layers(m->c) * 2 * m->c.n_heads;
+    return rows * ((uint64_t)s.len + (uint64_t)s.n_in) * m->c.head_dim * m->esz;
+}
+
+extern "C" int64_t exe_seq_export_bytes(exe_model_t* m, int32_t seq_id)
+{
+    if (!m) return fail(EXE_ERR_ARG, "null model");
+    if (seq_id < 0 || seq_id >= m->c.max_seqs || !m->seqs[seq_id].live) return fail(EXE_ERR_BAD_SEQ, "seq id %d is not live", seq_id);
+    return (int64_t)export_bytes_of(m, m->seqs[seq_id]);
+}
+
+extern "C" int exe_seq_export(exe_model_t* m, int32_t seq_id, void* host_buf, uint64_t buf_bytes, exe_seq_state_t* state)
+{
+    if (!m || !host_buf || !state) return fail(EXE_ERR_ARG, "null argument");
+    if (seq_id < 0 || seq_id >= m->c.max_seqs || !m->seqs[seq_id].live) return fail(EXE_ERR_BAD_SEQ, "seq id %d is not live", seq_id);
+    const Seq& s = m->seqs[seq_id];
+    uint64_t need = export_bytes_of(m, s);
+    if (buf_bytes < need) return fail(EXE_ERR_ARG, "buffer of %llu bytes, %llu needed", (unsigned long long)buf_bytes, (unsigned long long)need);
+    size_t rows = (size_t)n_dec_layers(m->c) * 2 * m->c.n_heads, rowb = (size_t)m->c.head_dim * m->esz;
+    char* dst = (char*)host_buf;
+    if (s.len > 0) {
+        HIP_TRY(hipMemcpy2DAsync(dst, s.len * rowb, (const char*)m->pool.ptr + s.base * m->esz, s.cap * rowb, s.len * rowb, rows,
+                                 hipMemcpyDeviceToHost, m->stream));
+        dst += rows * s.len * rowb;
+    }
+    if (s.n_in > 0)
+        HIP_TRY(hipMemcpy2DAsync(dst, s.n_in * rowb, (const char*)m->pool.ptr + s.xbase * m->esz, round8(s.n_in) * rowb,
+                                 s.n_in * rowb, rows, hipMemcpyDeviceToHost, m->stream));
+    HIP_TRY(hipStreamSynchronize(m->stream));
+    state->kv_len = s.len;
+    state->cross_len = s.n_in;
+    return EXE_OK;
+}
+
+extern "C" int exe_seq_import(exe_model_t* m, int32_t seq_id, const void* host_buf, uint64_t buf_bytes,
+                              const exe_seq_state_t* state, int32_t reserve_length)
+{
+    if (!m || !host_buf || !state) return fail(EXE_ERR_ARG, "null argument");
+    const exe_config_t& c = m->c;
+    if (seq_id < 0 || seq_id >= c.max_seqs) return fail(EXE_ERR_BAD_SEQ, "seq id %d out of range", seq_id);
+    if (m->seqs[seq_id].live) return fail(EXE_ERR_BAD_SEQ, "seq id %d is live", seq_id);
+    bool encdec = c.arch == EXE_ARCH_ENC_DEC;
+    bool learned = c.has_embed && c.pos == EXE_POS_LEARNED;
+    if (state->kv_len < 0 || state->cross_len < 0 || (encdec ? state->cross_len < 1 : (state->kv_len < 1 || state->cross_len != 0)))
+        return fail(EXE_ERR_BAD_LENGTH, "bad state: kv_len %d, cross_len %d", state->kv_len, state->cross_len);
+    if (learned && !encdec && state->kv_len > c.max_pos) return fail(EXE_ERR_BAD_LENGTH, "kv_len %d exceeds max_pos", state->kv_len);
+    Seq s;
+    s.len = state->kv_len;
+    s.n_in = state->cross_len;
+    if (buf_bytes < export_bytes_of(m, s)) return fail(EXE_ERR_ARG, "buffer of %llu bytes is too small for the state", (unsigned long long)buf_bytes);
+    int cap = reserve_length > 0 ? reserve_length : s.len + 256;
+    if (cap < std::max(s.len, 1)) return fail(EXE_ERR_BAD_LENGTH, "reserve length %d too small", cap);
+    if (learned && !encdec && cap > c.max_pos) cap = c.max_pos;
+    s.cap = round8(cap);
+    int ndl = n_dec_layers(c);
+    s.elems = (int64_t)ndl * 2 * m->inner * s.cap;
+    s.base = m->pool.alloc(s.elems);
+    if (s.base >= 0 && encdec) {
+        s.xelems = (int64_t)ndl * 2 * m->inner * round8(s.n_in);
+        s.xbase = m->pool.alloc(s.xelems);
+    }
+    if (s.base < 0 || (encdec && s.xbase < 0)) {
+        if (s.base >= 0) m->pool.release(s.base, s.elems);
+        return fail(EXE_ERR_OOM_KV, "K/V pool exhausted (%lld of %lld elements in use)", (long long)m->pool.used, (long long)m->pool.elems);
+    }
+    size_t rows = (size_t)ndl * 2 * c.n_heads, rowb = (size_t)c.head_dim * m->esz;
+    const char* src = (const char*)host_buf;
+    hipError_t e = hipSuccess;
+    if (s.len > 0) {
+        e = hipMemcpy2DAsync((char*)m->pool.ptr + s.base * m->esz, s.cap * rowb, src, s.len * rowb, s.len * rowb, rows,
+                             hipMemcpyHostToDevice, m->stream);
+        src += rows * s.len * rowb;
+    }
+    if (e == hipSuccess && s.n_in > 0)
+        e = hipMemcpy2DAsync((char*)m->pool.ptr + s.xbase * m->esz, round8(s.n_in) * rowb, src, s.n_in * rowb, s.n_in * rowb, rows,
+                             hipMemcpyHostToDevice, m->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    if (e != hipSuccess) {
+        m->pool.release(s.base, s.elems);
+        if (s.xbase >= 0) m->pool.release(s.xbase, s.xelems);
+        return fail(EXE_ERR_HIP, "K/V import copy: %s", hipGetErrorString(e));
+    }
+    s.live = true;
+    m->seqs[seq_id] = s;
+    m->live++;
+    return EXE_OK;
+}
+
 extern "C" int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used_bytes, uint64_t* largest_free_bytes,
                             int32_t* live_seqs)
 {
