@@ -101,18 +101,17 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-    for (int j0 = wave * RPW * U; j0 < nk; j0 += NWV * RPW * U) {
+    // with a fused append the cached rows are 0 .. nk-2; the new row is folded in after the loop
+    const int nc = (!PACKED && knew) ? nk - 1 : nk;
+    for (int j0 = wave * RPW * U; j0 < nc; j0 += NWV * RPW * U) {
         uint4 kc[U], vc[U];
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int j = j0 + u * RPW + rg;
-            int jj = j < nk ? j : nk - 1;
-            const T* kr = kp + (int64_t)jj * row_stride;
-            const T* vr = vp + (int64_t)jj * row_stride;
-            if (!PACKED && knew && jj == nk - 1) { kr = knew; vr = vnew; }
-            kc[u] = *(const uint4*)(kr + cl * EPL);
-            vc[u] = *(const uint4*)(vr + cl * EPL);
+            int jj = j < nc ? j : nc - 1;
+            kc[u] = *(const uint4*)(kp + (int64_t)jj * row_stride + cl * EPL);
+            vc[u] = *(const uint4*)(vp + (int64_t)jj * row_stride + cl * EPL);
         }
         float mx = m_run;
 #pragma unroll
@@ -130,7 +129,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
                 rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
                 d += bias[rel] * LOG2E;
             }
-            s[u] = j < nk ? d : -INFINITY;
+            s[u] = j < nc ? d : -INFINITY;
             mx = fmaxf(mx, s[u]);
         }
         float mref = mx == -INFINITY ? 0.f : mx;
@@ -147,6 +146,30 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
 #pragma unroll
             for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
         }
+        m_run = mx;
+    }
+
+    // the appended position (its key and value come from the projection output): folded into the state of the
+    // first row group of wave 0
+    if (!PACKED && knew && wave == 0 && rg == 0) {
+        float kf[EPL], vf[EPL];
+        Chunk<T, EPL>::unpack(*(const uint4*)(knew + cl * EPL), kf);
+        Chunk<T, EPL>::unpack(*(const uint4*)(vnew + cl * EPL), vf);
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kf[e], d);
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
+        if (bias) {
+            int rel = nk - 1 - qpos;
+            rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
+            d += bias[rel] * LOG2E;
+        }
+        float mx = fmaxf(m_run, d);
+        float alpha = fast_exp2(m_run - mx), p = fast_exp2(d - mx);
+        l_run = l_run * alpha + p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e] * alpha);
         m_run = mx;
     }
 
