@@ -213,25 +213,58 @@ hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s)
 }
 
 // ---------------------------------------------------------------- MFMA prefill (bf16, head size 128)
-constexpr int PF_DH = 128, PF_KT = 64;
+// A workgroup of 8 waves owns PREFILL_TILE_Q = 256 query rows of one (sequence, head), 32 per wave as two 16-row
+// blocks.  Keys and values pass through LDS in tiles of 64, double buffered: the key tile arrives by direct
+// global->LDS loads, the value tile through registers because it is stored transposed.  Per tile a wave computes
+//   S^T[key][query] = K . Q^T      (MFMA 16x16x32: A = key rows from LDS, B = the wave's query fragments)
+//   O^T[d][query]  += V^T . P^T    (A = transposed values from LDS, B = P straight from the accumulators of S^T)
+// so a query's softmax statistics live in the four lanes that share its column, and the probabilities never leave
+// registers.  One barrier per tile; two waves per SIMD let one wave's softmax overlap the other's MFMAs.
+constexpr int PF_DH = 128, PF_KT = 64, PF_THREADS = 512;
+constexpr int PF_KST = 3, PF_TILE = 16384, PF_LDS = (PF_KST + 2) * PF_TILE;
 
-// K tile [64 keys][128] in LDS: 256-byte rows of 16 chunks, chunk c of key r stored at slot c ^ (r & 15).
-__device__ __forceinline__ int pf_k_off(int key, int chunk) { return key * 256 + ((chunk ^ (key & 15)) << 4); }
-// V tile transposed [128 cols][64 keys]: 128-byte rows of 16 four-key groups (8 bytes each); group kq of
-// column c is stored at slot kq ^ swz(c).  swz makes both the 2-byte transposing writes (16 columns 8 apart,
-// one key) and the 8-byte operand reads (32 consecutive columns, one key group) spread over all banks.
-__device__ __forceinline__ int pf_swz(int c) { return ((c >> 1) & 15) ^ ((c >> 5) & 3); }
-__device__ __forceinline__ int pf_v_off(int c, int kq) { return c * 128 + ((kq ^ pf_swz(c)) << 3); }
+// A key or value tile [64 rows][128] in LDS: 256-byte rows of 16 chunks, chunk c of row r stored at slot c ^ (r & 15).
+__device__ __forceinline__ int pf_off(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+
+typedef __attribute__((ext_vector_type(4))) short pf_v4s;
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane L points at 4 consecutive 16-bit
+// elements M[L][0..3]; lane i receives M[4*j + i/4][i%4], j = 0..3.  With lane L = 4*j + q pointing at columns
+// d0 + 4*q .. +3 of row j, lane i ends up with column d0 + i of rows 0..3: four values along the row index for one
+// column, which is how an MFMA operand wants a row-major tile whose rows are the contraction index.
+__device__ __forceinline__ uint2 pf_read_tr(const unsigned char* p)
+{
+    pf_v4s r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) pf_v4s*)p);
+    return __builtin_bit_cast(uint2, r);
+}
+
+// Reductions over the four 16-lane rows of a wave (the lanes that share a column of a 16x16 accumulator tile),
+// with the row-swap instructions of gfx950: v_permlane16_swap exchanges rows 1 and 3 of its first operand with
+// rows 0 and 2 of its second, v_permlane32_swap the upper half of the first with the lower half of the second.
+__device__ __forceinline__ float rows_max(float x)
+{
+    unsigned u = __float_as_uint(x);
+    auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    u = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
+    auto b = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum(float x)
+{
+    unsigned u = __float_as_uint(x);
+    auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    u = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
 
 template <bool CAUSAL, bool BIAS>
-__global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
-                                                           const int32_t* __restrict__ cu,
-                                                           const int32_t* __restrict__ tiles, int H, float scale,
-                                                           const float* __restrict__ bias_by_dist, int radius,
-                                                           bf16_t* __restrict__ out)
+__global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
+                                                                  const int32_t* __restrict__ cu,
+                                                                  const int32_t* __restrict__ tiles, int H,
+                                                                  float scale, const float* __restrict__ bias_by_dist,
+                                                                  int radius, bf16_t* __restrict__ out)
 {
-    __shared__ __align__(16) unsigned char sK[PF_KT * 256];
-    __shared__ __align__(16) unsigned char sV[PF_DH * 128];
+    extern __shared__ __align__(16) unsigned char pf_smem[];      // 3 key tiles, then 2 value tiles
     __shared__ float sbias[BIAS ? 1024 : 1];
 
     int sb = tiles[blockIdx.x * 2], q0 = tiles[blockIdx.x * 2 + 1];
@@ -239,166 +272,220 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t* __restr
     int t0 = cu[sb], n = cu[sb + 1] - t0;
     int inner = H * PF_DH;
     int64_t ld = 3 * (int64_t)inner;
-    int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int qi = lane & 31, g = lane >> 5;
-    int qpos = q0 + wave * 32 + qi;
+    int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int qi = lane & 15, g = lane >> 4;
+    int wq0 = q0 + wave * 32;                                     // this wave's first query row
     const bf16_t* seq = qkv + (int64_t)t0 * ld + h * PF_DH;
 
     if (BIAS) {
-        for (int i = tid; i < 2 * radius + 1; i += 256)
+        for (int i = tid; i < 2 * radius + 1; i += PF_THREADS)
             sbias[i] = bias_by_dist[(int64_t)h * (2 * radius + 1) + i] * LOG2E;
     }
 
-    bf16x8 qf[8];
-    {
-        int qr = qpos < n ? qpos : n - 1;
+    // query fragments (B operand): lane (query qi, lane group g) holds features 32*ds + 8*g .. +7
+    bf16x8 qf[2][4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        int qr = wq0 + qb * 16 + qi;
+        qr = qr < n ? qr : n - 1;
         const bf16_t* qp = seq + (int64_t)qr * ld + g * 8;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) qf[kk] = *(const bf16x8*)(qp + kk * 16);
+        for (int ds = 0; ds < 4; ++ds) qf[qb][ds] = *(const bf16x8*)(qp + ds * 32);
     }
     int kend = n;
     if (CAUSAL) kend = q0 + PREFILL_TILE_Q < n ? q0 + PREFILL_TILE_Q : n;
     int n_tiles = (kend + PF_KT - 1) / PF_KT;
 
-    int ld_key = tid >> 4, ld_ch = tid & 15;
-    uint4 rk[4], rv[4];
-    auto load_global = [&](int kt) {
+    // ---- loaders.  Per tile of keys and of values a wave issues two 1 KB direct-to-LDS loads of 4 rows each; a
+    // lane fills slot lane%16 of its row with the chunk that the swizzle puts there.  Written as inline assembly
+    // so that the compiler does not order every later LDS read behind them.
+    unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)pf_smem;
+    const char* kbase = (const char*)(seq + inner);
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+    auto load_to_lds = [&](const char* src, unsigned voff, unsigned dst) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(src) : "memory", "m0");
+    };
+#pragma clang diagnostic pop
+    const char* vbase = (const char*)(seq + 2 * inner);
+    auto load_tile = [&](const char* base, int kt, unsigned dst) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            int key = kt * PF_KT + p * 16 + ld_key;
-            key = key < n ? key : n - 1;
-            const bf16_t* kp = seq + (int64_t)key * ld + inner + ld_ch * 8;
-            rk[p] = *(const uint4*)kp;
-            rv[p] = *(const uint4*)(kp + inner);
+        for (int p = 0; p < 2; ++p) {
+            int row = (p * 8 + wave) * 4;                         // first of the 4 tile rows of this load
+            int key = row + (lane >> 4);
+            int kg = kt * PF_KT + key;
+            kg = kg < n ? kg : n - 1;
+            unsigned voff = (unsigned)kg * (unsigned)(ld * 2) + (((lane & 15) ^ (key & 15)) << 4);
+            load_to_lds(base, voff, dst + row * 256);
         }
     };
-    auto store_lds = [&]() {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            int key = p * 16 + ld_key;
-            *(uint4*)(sK + pf_k_off(key, ld_ch)) = rk[p];
-            uint32_t w[4] = {rv[p].x, rv[p].y, rv[p].z, rv[p].w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                int c = ld_ch * 8 + e;
-                uint16_t val = (uint16_t)(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xffff);
-                *(uint16_t*)(sV + pf_v_off(c, key >> 2) + (key & 3) * 2) = val;
-            }
-        }
-    };
+    auto load_k = [&](int kt) { load_tile(kbase, kt, lds_base + (kt % PF_KST) * PF_TILE); };
+    auto load_v = [&](int kt) { load_tile(vbase, kt, lds_base + (PF_KST + (kt & 1)) * PF_TILE); };
 
-    f32x16 o_acc[4];
+    f32x4 o_acc[2][8];
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
+    for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[ct][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+        for (int dt = 0; dt < 8; ++dt) o_acc[qb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
     float sc = scale * LOG2E;
+    f32x4 s_acc[2][4];
 
-    load_global(0);
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        __syncthreads();            // everyone is done reading the previous tile
-        store_lds();
-        __syncthreads();
-        if (kt + 1 < n_tiles) load_global(kt + 1);
+    // a wave whose queries all lie before a tile's first key (causal) or past the sequence end has nothing to
+    // compute for that tile; it still moves its share of the tiles
+    auto active = [&](int kt) { return wq0 < n && (!CAUSAL || kt * PF_KT <= wq0 + 31); };
 
-        f32x16 s_acc[2];
+    // ---- the three phases of a tile
+    auto phase_s = [&](int kt) {
+        const unsigned char* sK = pf_smem + (kt % PF_KST) * PF_TILE;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int kb = 0; kb < 4; ++kb) {
+            s_acc[0][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            s_acc[1][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s_acc[t][r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                bf16x8 fk = *(const bf16x8*)(sK + pf_k_off(t * 32 + qi, kk * 2 + g));
-                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, qf[kk], s_acc[t], 0, 0, 0);
+            for (int ds = 0; ds < 4; ++ds) {
+                bf16x8 fk = *(const bf16x8*)(sK + pf_off(kb * 16 + qi, ds * 4 + g));
+                s_acc[0][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk, qf[0][ds], s_acc[0][kb], 0, 0, 0);
+                s_acc[1][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk, qf[1][ds], s_acc[1][kb], 0, 0, 0);
             }
         }
-        // element r of lane (qi, g) in s_acc[t]: key = kt*64 + t*32 + 8*(r/4) + 4*g + r%4, query qpos.
-        // Only tiles that straddle the sequence end or (causal) this wave's diagonal need the per-element mask.
-        bool edge = kt * PF_KT + PF_KT > n || (CAUSAL && kt * PF_KT + PF_KT - 1 > q0 + wave * 32);
-        float mx = -INFINITY;
-        if (BIAS || edge) {
+    };
+    // element r of lane (qi, g) in s_acc[qb][kb]: key = kt*64 + kb*16 + 4*g + r, query wq0 + qb*16 + qi.
+    // Only tiles that straddle the sequence end or (causal) this wave's diagonal need the per-element mask.
+    auto phase_softmax = [&](int kt) {
+        bool masked = BIAS || kt * PF_KT + PF_KT > n || (CAUSAL && kt * PF_KT + PF_KT - 1 > wq0);
+        float alpha[2];
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+        for (int qb = 0; qb < 2; ++qb) {
+            int qpos = wq0 + qb * 16 + qi;
+            float mx = -INFINITY;
+            if (masked) {
+                int key0 = kt * PF_KT + 4 * g;
+                asm volatile("" : "+v"(key0));      // keeps the mask arithmetic inside this branch
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int key = kt * PF_KT + t * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    float v = s_acc[t][r] * sc;
-                    if (BIAS) {
-                        int rel = key - qpos;
-                        rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
-                        v += sbias[rel + radius];
+                for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int key = key0 + kb * 16 + r;
+                        float v = s_acc[qb][kb][r] * sc;
+                        if (BIAS) {
+                            int rel = key - qpos;
+                            rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
+                            v += sbias[rel + radius];
+                        }
+                        bool ok = key < n && (!CAUSAL || key <= qpos);
+                        v = ok ? v : -INFINITY;
+                        s_acc[qb][kb][r] = v;
+                        mx = fmaxf(mx, v);
                     }
-                    bool ok = key < n && (!CAUSAL || key <= qpos);
-                    v = ok ? v : -INFINITY;
-                    s_acc[t][r] = v;
-                    mx = fmaxf(mx, v);
-                }
-        } else {
+            } else {
+                // the scale is positive: take the maximum of the raw scores and fold the scale into the exponent
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = s_acc[t][r] * sc;
-                    s_acc[t][r] = v;
-                    mx = fmaxf(mx, v);
-                }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-        float m_new = fmaxf(m_run, mx);
-        float mref = m_new == -INFINITY ? 0.f : m_new;
-        float alpha = fast_exp2(m_run - mref);
-        float rs = 0.f;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float p = fast_exp2(s_acc[t][r] - mref);
-                s_acc[t][r] = p;
-                rs += p;
+                    for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s_acc[qb][kb][r]);
+                mx *= sc;
             }
-        rs += __shfl_xor(rs, 32, WAVE);
-        l_run = l_run * alpha + rs;
-        m_run = m_new;
+            mx = rows_max(mx);
+            float m_new = fmaxf(m_run[qb], mx);
+            float mref = m_new == -INFINITY ? 0.f : m_new;
+            alpha[qb] = fast_exp2(m_run[qb] - mref);
+            float mul = masked ? 1.f : sc;
+            float rs = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float p = fast_exp2(fmaf(s_acc[qb][kb][r], mul, -mref));
+                    s_acc[qb][kb][r] = p;
+                    rs += p;
+                }
+            rs = rows_sum(rs);
+            l_run[qb] = l_run[qb] * alpha[qb] + rs;
+            m_run[qb] = m_new;
+        }
         // the running maximum of a query stops moving after the first tiles: rescale only when some lane needs it
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+        if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.f || alpha[1] != 1.f) != 0) {
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct)
+            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o_acc[ct][r] *= alpha;
+                for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o_acc[qb][dt][r] *= alpha[qb];
         }
-
-        // O^T += V^T . P^T.  MFMA k-step ks covers, in lane group g, the 8 keys held in accumulator
-        // elements 8*(ks%2) .. +7 of s_acc[ks/2]: key groups kq = (ks/2)*8 + (ks%2)*4 + g and kq + 2.
+    };
+    // O^T += V^T . P^T.  MFMA k-step ks covers keys 32*ks .. +31 of the tile; lane group g supplies keys
+    // 4*g .. +3 of key blocks 2*ks and 2*ks+1.  The value tile lies row-major (one key per row); the transposing
+    // read hands lane (qi, g) the column 16*dt + qi of those four keys: within the 16 lanes of a group, lane
+    // L = 4*j + q points at columns 16*dt + 4*q .. +3 of key 4*g + j.
+    int v_row = 4 * g + (qi >> 2), v_q = qi & 3;
+    auto phase_pv = [&](int kt) {
+        const unsigned char* sV = pf_smem + (PF_KST + (kt & 1)) * PF_TILE + v_row * 256 + (v_q & 1) * 8;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 pf;
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 pf[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[e] = (bf16_t)s_acc[ks >> 1][(ks & 1) * 8 + e];
-            int kq = (ks >> 1) * 8 + (ks & 1) * 4 + g;
+            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct) {
-                int c = ct * 32 + qi;
-                uint2 lo = *(const uint2*)(sV + pf_v_off(c, kq));
-                uint2 hi = *(const uint2*)(sV + pf_v_off(c, kq + 2));
+                for (int e = 0; e < 8; ++e) pf[qb][e] = (bf16_t)s_acc[qb][2 * ks + (e >> 2)][e & 3];
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                int slot = ((2 * dt + (v_q >> 1)) ^ v_row) << 4;     // rows v_row, +16, +32, +48 share their low 4 bits
+                uint2 lo = pf_read_tr(sV + ks * 32 * 256 + slot);
+                uint2 hi = pf_read_tr(sV + (ks * 32 + 16) * 256 + slot);
                 uint4 both = {lo.x, lo.y, hi.x, hi.y};
-                o_acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, o_acc[ct], 0, 0, 0);
+                bf16x8 fv = __builtin_bit_cast(bf16x8, both);
+                o_acc[0][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv, pf[0], o_acc[0][dt], 0, 0, 0);
+                o_acc[1][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv, pf[1], o_acc[1][dt], 0, 0, 0);
             }
         }
+    };
+
+    // The two waves that share a SIMD (wave w and w + 4) run half a tile apart, so that one is in its softmax
+    // (vector ALU) while the other issues MFMAs: waves 4..7 compute the scores of tile kt+1 at the end of
+    // iteration kt.  That is why key tiles are kept three deep: tile kt+1 is complete and published by the barrier
+    // that ends iteration kt-1, while tile kt+2 is on its way.
+#ifndef PF_AHEAD
+#define PF_AHEAD (wave >= 4)
+#endif
+    bool ahead = PF_AHEAD;
+    load_k(0);
+    load_v(0);
+    if (n_tiles > 1) load_k(1);
+    __builtin_amdgcn_s_waitcnt(0x0070 | (15 << 8));               // vmcnt(0)
+    __syncthreads();
+    if (ahead && active(0)) phase_s(0);
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        if (kt + 2 < n_tiles) load_k(kt + 2);
+        bool more = kt + 1 < n_tiles;
+        if (more) load_v(kt + 1);
+        bool act = active(kt);
+        if (!ahead && act) phase_s(kt);
+        if (act) {
+            phase_softmax(kt);
+            phase_pv(kt);
+        }
+        if (ahead && more && active(kt + 1)) phase_s(kt + 1);
+        __builtin_amdgcn_s_waitcnt(0x0070 | (15 << 8));           // this wave's parts of the next tiles have landed
+        __syncthreads();
     }
 
-    if (qpos < n) {
-        float inv = 1.f / l_run;
-        bf16_t* op = out + (int64_t)(t0 + qpos) * inner + h * PF_DH;
+    // lane (qi, g) holds features 16*dt + 4*g .. +3 of its query
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+    for (int qb = 0; qb < 2; ++qb) {
+        int qpos = wq0 + qb * 16 + qi;
+        if (qpos < n) {
+            float inv = 1.f / l_run[qb];
+            bf16_t* op = out + (int64_t)(t0 + qpos) * inner + h * PF_DH + 4 * g;
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
+            for (int dt = 0; dt < 8; ++dt) {
                 bf16x4 w;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) w[j] = (bf16_t)(o_acc[ct][q4 * 4 + j] * inv);
-                *(bf16x4*)(op + ct * 32 + q4 * 8 + g * 4) = w;
+                for (int j = 0; j < 4; ++j) w[j] = (bf16_t)(o_acc[qb][dt][j] * inv);
+                *(bf16x4*)(op + dt * 16) = w;
             }
+        }
     }
 }
 
@@ -407,19 +494,33 @@ bool prefill_mfma_supported(int dtype, int dh) { return dtype == DT_BF16 && dh =
 hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
+    // (the key loader addresses a sequence's rows with 32-bit byte offsets)
     if (!a.force_generic && prefill_mfma_supported(a.dtype, a.dh) && a.n_tiles > 0 &&
-        (!a.bias_by_dist || 2 * a.bias_radius + 1 <= 1024)) {
+        (int64_t)a.T * 3 * a.H * a.dh * 2 < ((int64_t)1 << 32) && (!a.bias_by_dist || 2 * a.bias_radius + 1 <= 1024)) {
         dim3 grid(a.n_tiles, a.H);
         const bf16_t* qkv = (const bf16_t*)a.qkv;
         bf16_t* out = (bf16_t*)a.out;
-        if (a.causal) {
-            if (a.bias_by_dist) prefill_mfma_kernel<true, true><<<grid, 256, 0, s>>>(qkv, a.cu, a.tiles, a.H, a.scale, a.bias_by_dist, a.bias_radius, out);
-            else prefill_mfma_kernel<true, false><<<grid, 256, 0, s>>>(qkv, a.cu, a.tiles, a.H, a.scale, nullptr, 0, out);
-        } else {
-            if (a.bias_by_dist) prefill_mfma_kernel<false, true><<<grid, 256, 0, s>>>(qkv, a.cu, a.tiles, a.H, a.scale, a.bias_by_dist, a.bias_radius, out);
-            else prefill_mfma_kernel<false, false><<<grid, 256, 0, s>>>(qkv, a.cu, a.tiles, a.H, a.scale, nullptr, 0, out);
+        constexpr int lds = PF_LDS;
+        static bool attr_set = false;
+        if (!attr_set) {
+            const void* kerns[4] = {(const void*)prefill_mfma_kernel<true, true>, (const void*)prefill_mfma_kernel<true, false>,
+                                    (const void*)prefill_mfma_kernel<false, true>, (const void*)prefill_mfma_kernel<false, false>};
+            for (const void* k : kerns) {
+                hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                if (e != hipSuccess) return e;
+            }
+            attr_set = true;
         }
-        return hipGetLastError();
+        auto launch = [&](auto kern, const float* bias, int radius) -> hipError_t {
+            kern<<<grid, PF_THREADS, lds, s>>>(qkv, a.cu, a.tiles, a.H, a.scale, bias, radius, out);
+            return hipGetLastError();
+        };
+        if (a.causal) {
+            if (a.bias_by_dist) return launch(prefill_mfma_kernel<true, true>, a.bias_by_dist, a.bias_radius);
+            return launch(prefill_mfma_kernel<true, false>, nullptr, 0);
+        }
+        if (a.bias_by_dist) return launch(prefill_mfma_kernel<false, true>, a.bias_by_dist, a.bias_radius);
+        return launch(prefill_mfma_kernel<false, false>, nullptr, 0);
     }
     dim3 grid(a.H, a.T);
 #define EXE_ROW(T, DH)                                                                                           \
