@@ -68,7 +68,7 @@ struct AttnPackedArgs {      // ragged prefill over packed qkv [T, 3*H*dh]
     int force_generic;
 };
 bool prefill_mfma_supported(int dtype, int dh);
-constexpr int PREFILL_TILE_Q = 256;
+constexpr int PREFILL_TILE_Q = 128;
 hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s);
 
 }  // namespace exe

@@ -9,8 +9,9 @@
 //                      head sizes); the MFMA kernel below replaces it for bf16 with head size 128.
 //  * prefill_mfma_kernel<CAUSAL, BIAS>: flash-style ragged prefill for bf16, head size 128.  A workgroup
 //    owns 128 query rows of one (sequence, head); keys/values go through LDS in tiles of 64.
-//    S^T = K.Q^T and O^T = V^T.P^T are both computed with MFMA 32x32x16 so that softmax statistics of a
-//    query live in one lane and P feeds the second MFMA straight from the first one's accumulators.
+//    S^T = K.Q^T and O^T = V^T.P^T are both computed with MFMA 16x16x32 so that softmax statistics of a
+//    query live in the lanes of one accumulator column and P feeds the second MFMA straight from the first
+//    one's accumulators.
 #include "common.h"
 #include "kernels.h"
 
@@ -213,15 +214,19 @@ hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s)
 }
 
 // ---------------------------------------------------------------- MFMA prefill (bf16, head size 128)
-// A workgroup of 8 waves owns PREFILL_TILE_Q = 256 query rows of one (sequence, head), 32 per wave as two 16-row
-// blocks.  Keys and values pass through LDS in tiles of 64, double buffered: the key tile arrives by direct
-// global->LDS loads, the value tile through registers because it is stored transposed.  Per tile a wave computes
+// A workgroup of 4 waves owns PREFILL_TILE_Q = 128 query rows of one (sequence, head), 32 per wave as two 16-row
+// blocks; two workgroups fit a CU.  Keys and values pass through LDS in tiles of 64 rows, double buffered, both
+// by direct global->LDS loads in the same row-major swizzled layout.  Per tile a wave computes
 //   S^T[key][query] = K . Q^T      (MFMA 16x16x32: A = key rows from LDS, B = the wave's query fragments)
-//   O^T[d][query]  += V^T . P^T    (A = transposed values from LDS, B = P straight from the accumulators of S^T)
+//   O^T[d][query]  += V^T . P^T    (A = values through the transposing LDS read, B = P straight from the
+//                                   accumulators of S^T)
 // so a query's softmax statistics live in the four lanes that share its column, and the probabilities never leave
-// registers.  One barrier per tile; two waves per SIMD let one wave's softmax overlap the other's MFMAs.
-constexpr int PF_DH = 128, PF_KT = 64, PF_THREADS = 512;
-constexpr int PF_KST = 3, PF_TILE = 16384, PF_LDS = (PF_KST + 2) * PF_TILE;
+// registers.  One barrier per tile.  The two workgroups of a CU drift apart, so one wave's softmax (vector ALU)
+// overlaps another's MFMAs on the same SIMD.
+constexpr int PF_NW = 4, PF_DH = 128, PF_KT = 64, PF_THREADS = PF_NW * 64, PF_QT = PF_NW * 32;
+constexpr int PF_LPT = 16 / PF_NW;                                // direct-to-LDS loads per wave and tile
+constexpr int PF_TILE = 16384, PF_LDS = 3 * PF_TILE;              // key tiles 0 and 1, then the value tile
+static_assert(PF_QT == PREFILL_TILE_Q, "the tile list is built for PREFILL_TILE_Q query rows per workgroup");
 
 // A key or value tile [64 rows][128] in LDS: 256-byte rows of 16 chunks, chunk c of row r stored at slot c ^ (r & 15).
 __device__ __forceinline__ int pf_off(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
@@ -258,13 +263,13 @@ __device__ __forceinline__ float rows_sum(float x)
 }
 
 template <bool CAUSAL, bool BIAS>
-__global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(PF_THREADS, 3) void prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
                                                                   const int32_t* __restrict__ cu,
                                                                   const int32_t* __restrict__ tiles, int H,
                                                                   float scale, const float* __restrict__ bias_by_dist,
                                                                   int radius, bf16_t* __restrict__ out)
 {
-    extern __shared__ __align__(16) unsigned char pf_smem[];      // 3 key tiles, then 2 value tiles
+    extern __shared__ __align__(16) unsigned char pf_smem[];      // 2 key tiles, then 2 value tiles
     __shared__ float sbias[BIAS ? 1024 : 1];
 
     int sb = tiles[blockIdx.x * 2], q0 = tiles[blockIdx.x * 2 + 1];
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* 
         for (int ds = 0; ds < 4; ++ds) qf[qb][ds] = *(const bf16x8*)(qp + ds * 32);
     }
     int kend = n;
-    if (CAUSAL) kend = q0 + PREFILL_TILE_Q < n ? q0 + PREFILL_TILE_Q : n;
+    if (CAUSAL) kend = q0 + PF_QT < n ? q0 + PF_QT : n;
     int n_tiles = (kend + PF_KT - 1) / PF_KT;
 
     // ---- loaders.  Per tile of keys and of values a wave issues two 1 KB direct-to-LDS loads of 4 rows each; a
@@ -310,8 +315,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* 
     const char* vbase = (const char*)(seq + 2 * inner);
     auto load_tile = [&](const char* base, int kt, unsigned dst) {
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            int row = (p * 8 + wave) * 4;                         // first of the 4 tile rows of this load
+        for (int p = 0; p < 16 / PF_NW; ++p) {
+            int row = (p * PF_NW + wave) * 4;                       // first of the 4 tile rows of this load
             int key = row + (lane >> 4);
             int kg = kt * PF_KT + key;
             kg = kg < n ? kg : n - 1;
@@ -319,8 +324,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* 
             load_to_lds(base, voff, dst + row * 256);
         }
     };
-    auto load_k = [&](int kt) { load_tile(kbase, kt, lds_base + (kt % PF_KST) * PF_TILE); };
-    auto load_v = [&](int kt) { load_tile(vbase, kt, lds_base + (PF_KST + (kt & 1)) * PF_TILE); };
+    auto load_k = [&](int kt) { load_tile(kbase, kt, lds_base + (kt & 1) * PF_TILE); };
+    auto load_v = [&](int kt) { load_tile(vbase, kt, lds_base + 2 * PF_TILE); };
 
     f32x4 o_acc[2][8];
 #pragma unroll
@@ -337,7 +342,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* 
 
     // ---- the three phases of a tile
     auto phase_s = [&](int kt) {
-        const unsigned char* sK = pf_smem + (kt % PF_KST) * PF_TILE;
+        const unsigned char* sK = pf_smem + (kt & 1) * PF_TILE;
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
             s_acc[0][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -420,7 +425,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* 
     // L = 4*j + q points at columns 16*dt + 4*q .. +3 of key 4*g + j.
     int v_row = 4 * g + (qi >> 2), v_q = qi & 3;
     auto phase_pv = [&](int kt) {
-        const unsigned char* sV = pf_smem + (PF_KST + (kt & 1)) * PF_TILE + v_row * 256 + (v_q & 1) * 8;
+        const unsigned char* sV = pf_smem + 2 * PF_TILE + v_row * 256 + (v_q & 1) * 8;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             bf16x8 pf[2];
@@ -441,33 +446,26 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_mfma_kernel(const bf16_t* 
         }
     };
 
-    // The two waves that share a SIMD (wave w and w + 4) run half a tile apart, so that one is in its softmax
-    // (vector ALU) while the other issues MFMAs: waves 4..7 compute the scores of tile kt+1 at the end of
-    // iteration kt.  That is why key tiles are kept three deep: tile kt+1 is complete and published by the barrier
-    // that ends iteration kt-1, while tile kt+2 is on its way.
-#ifndef PF_AHEAD
-#define PF_AHEAD (wave >= 4)
-#endif
-    bool ahead = PF_AHEAD;
+    // Key tiles are double buffered; the single value tile is loaded at the start of its own iteration, behind
+    // the scores and the softmax, which costs a second barrier per tile but lets three workgroups share a CU.
     load_k(0);
-    load_v(0);
-    if (n_tiles > 1) load_k(1);
     __builtin_amdgcn_s_waitcnt(0x0070 | (15 << 8));               // vmcnt(0)
     __syncthreads();
-    if (ahead && active(0)) phase_s(0);
 
     for (int kt = 0; kt < n_tiles; ++kt) {
-        if (kt + 2 < n_tiles) load_k(kt + 2);
+        load_v(kt);                                               // PF_LPT loads
         bool more = kt + 1 < n_tiles;
-        if (more) load_v(kt + 1);
+        if (more) load_k(kt + 1);                                 // PF_LPT loads, into the buffer tile kt-1 has left
         bool act = active(kt);
-        if (!ahead && act) phase_s(kt);
         if (act) {
+            phase_s(kt);
             phase_softmax(kt);
-            phase_pv(kt);
         }
-        if (ahead && more && active(kt + 1)) phase_s(kt + 1);
-        __builtin_amdgcn_s_waitcnt(0x0070 | (15 << 8));           // this wave's parts of the next tiles have landed
+        if (more) __builtin_amdgcn_s_waitcnt(0x0070 | PF_LPT | (15 << 8));   // the value tile: all but the key loads
+        else __builtin_amdgcn_s_waitcnt(0x0070 | (15 << 8));
+        __syncthreads();
+        if (act) phase_pv(kt);
+        __builtin_amdgcn_s_waitcnt(0x0070 | (15 << 8));           // this wave's part of the next key tile has landed
         __syncthreads();
     }
 
