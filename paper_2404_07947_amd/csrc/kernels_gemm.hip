@@ -226,8 +226,12 @@ template <int BM, int BN, int WM, int WN, int ST>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias,
     int act, float alpha, int out_mode, void* __restrict__ out, float* __restrict__ partial, int tiles_m, int tiles_n,
-    int k_per_split, int n_split, int spread)
+    int k_per_split, int n_split, int flags)
 {
+    // flags: bit 0 = spread the loads of a k-tile over the MFMAs (see below); bit 1 = the weights are read once
+    // (a single row of output tiles): their loads are marked nontemporal so that they do not displace A in L2
+    const int spread = flags & 1;
+    const bool w_once = (flags & 2) != 0;
     constexpr int NW = (BM / WM) * (BN / WN);
     constexpr int TM = WM / 16, TN = WN / 16;       // 16x16 accumulator tiles of a wave: TM along rows, TN along features
     constexpr int MH = TM > 2 ? TM / 2 : 1;         // row parts of the wave's tile, one per sub-step
@@ -309,6 +313,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     auto load_to_lds = [&](const char* src, unsigned voff, unsigned dst) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(src) : "memory", "m0");
     };
+    auto load_to_lds_nt = [&](const char* src, unsigned voff, unsigned dst) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dst), "v"(voff), "s"(src) : "memory", "m0");
+    };
 #pragma clang diagnostic pop
     auto issue_range = [&](int stage, auto x0, auto x1) {
         unsigned base = lds_base + stage * STAGE + wave * 1024;
@@ -317,6 +324,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 #pragma unroll
         for (int x = decltype(x0)::value; x < decltype(x1)::value; ++x) {
             if (x < A_PASSES) load_to_lds(ka, off_a[x], base + x * NW * 1024);
+            else if (w_once) load_to_lds_nt(kw, off_w[x - A_PASSES], base + BM * TBK * 2 + (x - A_PASSES) * NW * 1024);
             else load_to_lds(kw, off_w[x - A_PASSES], base + BM * TBK * 2 + (x - A_PASSES) * NW * 1024);
         }
     };
@@ -675,8 +683,12 @@ static hipError_t launch_tile(const GemmArgs& a, const Plan& p, hipStream_t s)
     int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
     int items = tm * tn * p.splits;
     int grid = items < persistent_grid() ? items : persistent_grid();
+    int w_once = tm == 1 && a.M <= 64;      // measured: 7-10 % faster up to 32 rows, even from 96 rows on
+    int force_nt = env_int("EXE_GEMM_NT", -1);
+    if (force_nt >= 0) w_once = force_nt != 0;
     kern<<<grid, threads, lds, s>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.W, (const bf16_t*)a.bias, a.act,
-                                    a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split, p.splits, p.spread);
+                                    a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split, p.splits,
+                                    (p.spread ? 1 : 0) | (w_once ? 2 : 0));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     int64_t quads = ((int64_t)a.M * a.N) / 4;
