@@ -50,6 +50,7 @@ struct AttnCacheArgs {       // one query row per batch entry against that seque
     // q + b*q_stride + new_k_off + head*dh and ... + new_v_off; the kernel stores them at position len-1 of the
     // cache and attends to them straight from there (new_k_off = 0 disables)
     int new_k_off = 0, new_v_off = 0;
+    int mean_len = 0;                      // average of len over the batch (0 = unknown): picks the launch shape
 };
 hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s);
 

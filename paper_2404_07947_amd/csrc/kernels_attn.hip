@@ -18,6 +18,7 @@
 namespace exe {
 
 constexpr float LOG2E = 1.44269504088896340736f;
+constexpr int ATTN_SHORT_LEN = 320;      // decode attention: mean rows per sequence up to which 4 waves serve a row
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -210,18 +211,27 @@ hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s)
     if (a.B <= 0) return hipSuccess;
     dim3 grid(a.H, a.B);
     // 16 waves per (sequence, head), 2 row blocks in flight per wave: measured best of a sweep over
-    // {1,2,4,8,16} waves x {1,2,3,4,8} blocks (6.4 TB/s at batch 256, 6.0 at batch 32; 4 waves x 4: 6.0 / 5.3)
-#define EXE_ROW(T, DH)                                                                                          \
-    attn_row_kernel<T, DH, false, 16, 2><<<grid, 1024, 0, s>>>((const T*)a.q, a.q_stride, (const T*)a.pool,     \
+    // {1,2,4,8,16} waves x {1,2,3,4,8} blocks (6.4 TB/s at batch 256, 6.0 at batch 32; 4 waves x 4: 6.0 / 5.3).
+    // Short sequences (mean_len rows on average, 0 = unknown) leave most of 16 waves without a row: 4 waves serve
+    // them better (32 rows: 6.3 against 2.2 TB/s, cache-assisted; even at about 300 rows).
+    int nwv = a.mean_len > 0 && a.mean_len <= ATTN_SHORT_LEN ? 4 : 16;
+#define EXE_ROW_N(T, DH, NWV)                                                                                   \
+    attn_row_kernel<T, DH, false, NWV, 2><<<grid, NWV * 64, 0, s>>>((const T*)a.q, a.q_stride, (const T*)a.pool, \
                                                                a.base, a.cap, a.len, a.qpos, nullptr, nullptr,  \
                                                                a.layer, a.H, 0, a.scale, a.bias_by_dist,        \
                                                                a.bias_radius, (T*)a.out, a.new_k_off, a.new_v_off)
+#define EXE_ROW(T, DH)                                                                                          \
+    do {                                                                                                        \
+        if (nwv == 4) EXE_ROW_N(T, DH, 4);                                                                      \
+        else EXE_ROW_N(T, DH, 16);                                                                              \
+    } while (0)
     if (a.dtype == DT_F32 && a.dh == 64) EXE_ROW(float, 64);
     else if (a.dtype == DT_F32 && a.dh == 128) EXE_ROW(float, 128);
     else if (a.dtype == DT_BF16 && a.dh == 64) EXE_ROW(bf16_t, 64);
     else if (a.dtype == DT_BF16 && a.dh == 128) EXE_ROW(bf16_t, 128);
     else return hipErrorInvalidValue;
 #undef EXE_ROW
+#undef EXE_ROW_N
     return hipGetLastError();
 }
 

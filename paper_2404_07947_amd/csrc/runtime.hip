@@ -738,6 +738,7 @@ struct DecodeDesc {
     int32_t *tok, *pos, *len, *cap, *xcap, *xlen;
     int64_t *base, *xbase;
     double self_bytes, self_flops, x_bytes, x_flops;
+    int mean_len, mean_xlen;      // average self / cross rows per sequence
 };
 
 static void fill_decode_desc(exe_model* m, Stager& st, DecodeDesc& d, const std::vector<DecodeSeq>& ds)
@@ -765,6 +766,8 @@ static void fill_decode_desc(exe_model* m, Stager& st, DecodeDesc& d, const std:
         sum_x += ds[i].n_in;
     }
     double e = esz_of(m);
+    d.mean_len = n > 0 ? (int)(sum_len / n + 0.5) : 0;
+    d.mean_xlen = n > 0 ? (int)(sum_x / n + 0.5) : 0;
     d.self_bytes = (2.0 * sum_len + 2.0 * n) * m->inner * e;
     d.self_flops = 4.0 * sum_len * m->inner;
     d.x_bytes = (2.0 * sum_x + 2.0 * n) * m->inner * e;
@@ -805,6 +808,7 @@ static int decode_layer(exe_model* m, const DecLayerW& L, int layer, int n, cons
                         layer, attn_scale(m), encdec ? m->bias_dec : nullptr, m->radius, m->ctx};
         a.new_k_off = m->inner;
         a.new_v_off = 2 * m->inner;
+        a.mean_len = d.mean_len;
         LAUNCH(m, EXE_K_DECODE_ATTN, d.self_bytes, d.self_flops, launch_attn_cache(a, m->stream));
     }
     if (parts & 1)
@@ -817,6 +821,7 @@ static int decode_layer(exe_model* m, const DecLayerW& L, int layer, int n, cons
         if (parts & 2) {
             AttnCacheArgs x{c.dtype, n, c.n_heads, c.head_dim, m->qkv, m->inner, m->pool.ptr, d.xbase, d.xcap, d.xlen, d.pos,
                             layer, attn_scale(m), m->bias_x, m->radius, m->ctx};
+            x.mean_len = d.mean_xlen;
             LAUNCH(m, EXE_K_CROSS_ATTN, d.x_bytes, d.x_flops, launch_attn_cache(x, m->stream));
         }
         if (parts & 1)
