@@ -546,11 +546,13 @@ static int env_int(const char* name, int dflt)
     return v ? atoi(v) : dflt;
 }
 
-// Cost model behind the choice of tile shape and split count (fitted to a sweep of the six shapes x 1..16 splits on
-// MI355X for 16 <= M <= 1024; its pick is within 1 % of the best on average, 7 % at worst): a workgroup's time is
-// the larger of its LDS-fill traffic at the rate one CU sustains through its vector L1 (about 45 GB/s) and its MFMA
-// work at the rate the tile loop reaches (about 4.5 TFLOP/s per CU); workgroups run in rounds of one per CU; the
-// whole launch cannot beat streaming W once from HBM; split-K adds the float partials' round trip and a second launch.
+// Cost model behind the choice of tile shape and split count, fitted to sweeps of the six shapes x 1..16 splits on
+// MI355X with the weights coming from HBM (the GEMM shapes of three models, 16 <= M <= 1024; the time of its picks
+// is within 1 % of the time of the best picks in total, 13 % at worst): a workgroup's time is the larger of its
+// LDS-fill traffic at the rate one CU sustains through its vector L1 (about 35 GB/s) and its MFMA work at the rate
+// the tile loop reaches on such short runs (about 3.5 TFLOP/s per CU; the 128 x 256 shape 0.8 of that); workgroups
+// run in rounds of one per CU; the whole launch cannot beat streaming W once from HBM; split-K adds the float
+// partials' round trip and a second launch.
 static double plan_cost(int cfg, int splits, int M, int N, int K)
 {
     int bm = CFG[cfg].bm, bn = CFG[cfg].bn;
@@ -558,10 +560,10 @@ static double plan_cost(int cfg, int splits, int M, int N, int K)
     int64_t wgs = tiles * splits;
     double rounds = (double)((wgs + 255) / 256);
     double ktiles = (double)((K / TBK + splits - 1) / splits);
-    double fill = ktiles * (bm + bn) * TBK * 2 / 45e9;
-    double mfma = ktiles * 2.0 * bm * bn * TBK / 4.5e12;
+    double fill = ktiles * (bm + bn) * TBK * 2 / 35e9;
+    double mfma = ktiles * 2.0 * bm * bn * TBK / (cfg == C128x256 ? 2.8e12 : 3.5e12);
     double t = rounds * (fill > mfma ? fill : mfma);
-    double hbm = (double)N * K * 2 / 5e12;
+    double hbm = (double)N * K * 2 / 5.5e12;
     if (t < hbm) t = hbm;
     t += 4e-6;
     if (splits > 1) t += 2.0 * splits * M * N * 4 / 3e12 + 1e-6;
