@@ -91,7 +91,7 @@ def accumulate(acc, rows):
 
 # HBM-side bytes (rocprofv3 FETCH_SIZE x 2 + WRITE_SIZE, factors from a plain copy) per algorithmic byte, measured
 # per kernel at the OPT-13B bench shapes (profiles/traffic_opt13b_kernels.md); None = not measured
-TRAFFIC_RATIO = {"gemm_tile": 5.3, "decode_attn": 1.0, "cross_attn": 1.0, "prefill_attn": 1.78}
+TRAFFIC_RATIO = {"gemm_tile": 5.25, "decode_attn": 1.0, "cross_attn": 1.0, "prefill_attn": 1.64}
 
 
 def roofline_entry(kind, a):
