@@ -221,7 +221,9 @@ def test_prefill_attention(dtype, dh, H, generic, causal, use_bias):
     rng = np.random.default_rng(19)
     worst = 0.0
     for s, L in enumerate(lens):
-        for i in sorted(set([0, L - 1] + list(rng.integers(0, L, 4)))):
+        # the MFMA kernel spreads a tile's rows over waves, 16-row blocks and lane groups: every row is checked
+        every_row = dtype == BF16 and dh == 128 and not generic
+        for i in (range(L) if every_row else sorted(set([0, L - 1] + list(rng.integers(0, L, 4))))):
             for h in range(H):
                 t = cu[s] + i
                 nk = i + 1 if causal else L
