@@ -154,6 +154,24 @@ int exe_seq_export(exe_model_t* m, int32_t seq_id, void* host_buf, uint64_t buf_
 int exe_seq_import(exe_model_t* m, int32_t seq_id, const void* host_buf, uint64_t buf_bytes,
                    const exe_seq_state_t* state, int32_t reserve_length);
 
+/*
+ * Extent relocation and compaction (Section 3 "XRunner": early termination of completed queries comes with the
+ * compaction of the key/value cache entries of the terminated ones).  A sequence's entries live in one extent of the
+ * pool with room for a reserved number of positions, so terminated sequences leave holes of different sizes.
+ *  exe_seq_reserve moves a live sequence's self-attention entries into a new extent with room for reserve_length
+ *    positions (>= its current length, rounded up to 8; growing lets a sequence outlive its first reservation,
+ *    shrinking returns capacity it will not use).  EXE_ERR_BAD_SEQ, EXE_ERR_BAD_LENGTH (shorter than the current
+ *    length, or beyond the position table), EXE_ERR_OOM_KV (no free extent of that size; nothing changes).
+ *  exe_kv_compact slides the extents of all live sequences towards the start of the pool, in address order, so
+ *    that the free space becomes one piece; *moved_bytes (nullable) receives the bytes copied.  An extent whose
+ *    move would overlap itself is copied in pieces no longer than the distance moved; one that would need more
+ *    than 64 pieces stays where it is.
+ * Both enqueue device-to-device copies on the model's stream, in order with the model's kernels, and return
+ * without waiting; sequence ids, lengths and results of later calls are unchanged by them.
+ */
+int exe_seq_reserve(exe_model_t* m, int32_t seq_id, int32_t reserve_length);
+int exe_kv_compact(exe_model_t* m, uint64_t* moved_bytes);
+
 /* Pool accounting (bytes). Any pointer may be NULL. */
 int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used_bytes, uint64_t* largest_free_bytes,
                  int32_t* live_seqs);

@@ -12,7 +12,7 @@ _lib = None
 
 DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
-    "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_profile", "exe_run_rra", "exe_kernel_timing",
+    "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_seq_reserve", "exe_kv_compact", "exe_profile", "exe_run_rra", "exe_kernel_timing",
     "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_norm", "exe_op_prefill_attention",
     "exe_op_decode_attention", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
     # exe_sched.h (host only)
@@ -127,6 +127,8 @@ def lib():
     L.exe_seq_export_bytes.restype = C.c_int64
     L.exe_seq_export.argtypes = [vp, i32, vp, C.c_uint64, C.POINTER(SeqState)]
     L.exe_seq_import.argtypes = [vp, i32, vp, C.c_uint64, C.POINTER(SeqState), i32]
+    L.exe_seq_reserve.argtypes = [vp, i32, i32]
+    L.exe_kv_compact.argtypes = [vp, C.POINTER(C.c_uint64)]
     L.exe_profile.argtypes = [vp, i32, ip, i32, ip, i32, C.POINTER(LengthDist), i32, C.POINTER(ProfileRow), i32, ip]
     L.exe_run_rra.argtypes = [vp, C.POINTER(RraConfig), i32, ip, ip, ip, ip, C.POINTER(RraStats)]
     L.exe_kernel_timing.argtypes = [vp, i32]
@@ -282,6 +284,15 @@ class Model:
         buf = np.ascontiguousarray(buf, dtype=np.uint8)
         st = SeqState(state["kv_len"], state["cross_len"])
         _check(lib().exe_seq_import(self._h, seq_id, buf.ctypes.data_as(C.c_void_p), buf.nbytes, C.byref(st), reserve_length))
+
+    def seq_reserve(self, seq_id: int, reserve_length: int) -> None:
+        _check(lib().exe_seq_reserve(self._h, seq_id, reserve_length))
+
+    def kv_compact(self) -> int:
+        """Returns the bytes moved."""
+        moved = C.c_uint64()
+        _check(lib().exe_kv_compact(self._h, C.byref(moved)))
+        return moved.value
 
     def run_rra(self, decode_batch: int, n_decode: int, input_lengths, output_lengths, tokens_packed,
                 max_encode_batch: int = 32, adjust: bool = False, workload_tolerance: float = 0.25):

@@ -996,6 +996,91 @@ extern "C" int exe_seq_import(exe_model_t* m, int32_t seq_id, const void* host_b
     return EXE_OK;
 }
 
+// ---------------------------------------------------------------- extent relocation and compaction
+extern "C" int exe_seq_reserve(exe_model_t* m, int32_t seq_id, int32_t reserve_length)
+{
+    if (!m) return fail(EXE_ERR_ARG, "null model");
+    const exe_config_t& c = m->c;
+    if (seq_id < 0 || seq_id >= c.max_seqs || !m->seqs[seq_id].live) return fail(EXE_ERR_BAD_SEQ, "seq id %d is not live", seq_id);
+    Seq& s = m->seqs[seq_id];
+    bool learned = c.has_embed && c.pos == EXE_POS_LEARNED;
+    if (reserve_length < std::max(s.len, 1)) return fail(EXE_ERR_BAD_LENGTH, "reserve length %d below the current length %d", reserve_length, s.len);
+    if (learned && c.arch != EXE_ARCH_ENC_DEC && reserve_length > c.max_pos)
+        return fail(EXE_ERR_BAD_LENGTH, "reserve length %d exceeds max_pos %d", reserve_length, c.max_pos);
+    int cap = round8(reserve_length);
+    if (cap == s.cap) return EXE_OK;
+    int64_t elems = (int64_t)n_dec_layers(c) * 2 * m->inner * cap;
+    int64_t base = m->pool.alloc(elems);
+    if (base < 0) return fail(EXE_ERR_OOM_KV, "no free extent of %lld elements (largest %lld)", (long long)elems, (long long)m->pool.largest());
+    size_t rows = (size_t)n_dec_layers(c) * 2 * c.n_heads, rowb = (size_t)c.head_dim * m->esz;
+    if (s.len > 0) {
+        hipError_t e = hipMemcpy2DAsync((char*)m->pool.ptr + base * m->esz, cap * rowb, (const char*)m->pool.ptr + s.base * m->esz,
+                                        s.cap * rowb, s.len * rowb, rows, hipMemcpyDeviceToDevice, m->stream);
+        if (e != hipSuccess) {
+            m->pool.release(base, elems);
+            return fail(EXE_ERR_HIP, "K/V relocation copy: %s", hipGetErrorString(e));
+        }
+    }
+    m->pool.release(s.base, s.elems);
+    s.base = base;
+    s.elems = elems;
+    s.cap = cap;
+    return EXE_OK;
+}
+
+extern "C" int exe_kv_compact(exe_model_t* m, uint64_t* moved_bytes)
+{
+    if (!m) return fail(EXE_ERR_ARG, "null model");
+    if (moved_bytes) *moved_bytes = 0;
+    struct Ext { int64_t base, elems; int seq; bool cross; };
+    std::vector<Ext> ex;
+    for (int i = 0; i < m->c.max_seqs; ++i) {
+        const Seq& s = m->seqs[i];
+        if (!s.live) continue;
+        if (s.base >= 0 && s.elems > 0) ex.push_back({s.base, s.elems, i, false});
+        if (s.xbase >= 0 && s.xelems > 0) ex.push_back({s.xbase, s.xelems, i, true});
+    }
+    std::sort(ex.begin(), ex.end(), [](const Ext& a, const Ext& b) { return a.base < b.base; });
+    // the free list is what lies between the extents
+    auto rebuild_free = [&]() {
+        m->pool.free_.clear();
+        int64_t at = 0;
+        for (const Ext& e : ex) {
+            if (e.base > at) m->pool.free_[at] = e.base - at;
+            at = e.base + e.elems;
+        }
+        if (m->pool.elems > at) m->pool.free_[at] = m->pool.elems - at;
+    };
+    int64_t end = 0;           // first element not occupied by the extents placed so far
+    uint64_t moved = 0;
+    for (Ext& e : ex) {
+        int64_t shift = e.base - end;
+        if (shift > 0 && (e.elems + shift - 1) / shift <= 64) {
+            // forward move in pieces that do not overlap their own source
+            for (int64_t o = 0; o < e.elems; o += shift) {
+                int64_t n = std::min(shift, e.elems - o);
+                hipError_t h = hipMemcpyAsync((char*)m->pool.ptr + (end + o) * m->esz, (const char*)m->pool.ptr + (e.base + o) * m->esz,
+                                              (size_t)n * m->esz, hipMemcpyDeviceToDevice, m->stream);
+                if (h != hipSuccess) {
+                    // a device error: this extent stays registered where it was (its entries may be damaged where
+                    // the pieces already enqueued overlap it); the extents moved before it keep their new places
+                    (void)hipStreamSynchronize(m->stream);
+                    rebuild_free();
+                    return fail(EXE_ERR_HIP, "K/V compaction copy: %s", hipGetErrorString(h));
+                }
+            }
+            moved += (uint64_t)e.elems * m->esz;
+            Seq& s = m->seqs[e.seq];
+            if (e.cross) s.xbase = end; else s.base = end;
+            e.base = end;
+        }
+        end = e.base + e.elems;
+    }
+    rebuild_free();
+    if (moved_bytes) *moved_bytes = moved;
+    return EXE_OK;
+}
+
 extern "C" int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used_bytes, uint64_t* largest_free_bytes,
                             int32_t* live_seqs)
 {
