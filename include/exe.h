@@ -286,6 +286,21 @@ int exe_op_decode_attention(void* hip_stream, int32_t dtype, int32_t B, const vo
                             const void* kv, const int64_t* k_offset, const int32_t* cap, const int32_t* len,
                             const int32_t* qpos, int32_t H, int32_t dh, float scale,
                             const float* bias_by_dist, int32_t bias_radius, void* out);
+/* Decode attention over a paged cache (Section 2: paging applied to the key/value memorization cache; the
+ * evaluation notes that paging would further help WAA scheduling): as exe_op_decode_attention, but the entries of one
+ * layer live in blocks of block_size positions (a power of two in [8, 4096]).  Block b starts at
+ * kv_blocks + b * 2*H*block_size*dh elements and holds [K|V][H][block_size][dh]; block_table [B, max_blocks] (device)
+ * lists each sequence's blocks in position order, so position p of sequence b is row p % block_size of block
+ * block_table[b][p / block_size].  new_kv_offset > 0: the newest position (len[b] - 1) is not in the cache yet; its
+ * key / value rows of (b, head) are read from q + b*q_stride + new_kv_offset + head*dh and
+ * q + b*q_stride + 2*new_kv_offset + head*dh and stored into the cache by this call (q then is the packed output of
+ * the QKV projection).  The caller guarantees that every table entry a sequence needs names a block inside the pool
+ * and that no block is shared between sequences. */
+int exe_op_decode_attention_paged(void* hip_stream, int32_t dtype, int32_t B, const void* q, int32_t q_stride,
+                                  const void* kv_blocks, const int32_t* block_table, int32_t max_blocks,
+                                  int32_t block_size, const int32_t* len, const int32_t* qpos, int32_t H, int32_t dh,
+                                  float scale, const float* bias_by_dist, int32_t bias_radius, int32_t new_kv_offset,
+                                  void* out);
 /* argmax over each row of float logits [rows, n] -> int32 out [rows]; lowest index on ties */
 int exe_op_argmax(void* hip_stream, const float* logits, int32_t rows, int32_t n, int32_t* out);
 /* T5 bucket of rel = key - query as this library computes it (host function, exact integer arithmetic) */

@@ -14,7 +14,7 @@ DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
     "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_seq_reserve", "exe_kv_compact", "exe_profile", "exe_run_rra", "exe_kernel_timing",
     "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_norm", "exe_op_prefill_attention",
-    "exe_op_decode_attention", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
+    "exe_op_decode_attention", "exe_op_decode_attention_paged", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
     # exe_sched.h (host only)
     "exe_sim_completion", "exe_sim_step_ms", "exe_sim_rra", "exe_sim_waa", "exe_sched_search", "exe_sched_rra",
 ]
@@ -139,6 +139,8 @@ def lib():
     L.exe_op_norm.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, C.c_float, C.c_float, vp]
     L.exe_op_prefill_attention.argtypes = [vp, i32, i32, ip, vp, i32, i32, C.c_float, i32, vp, i32, vp, i32]
     L.exe_op_decode_attention.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, vp, i32, vp]
+    L.exe_op_decode_attention_paged.argtypes = [vp, i32, i32, vp, i32, vp, vp, i32, i32, vp, vp, i32, i32, C.c_float, vp, i32,
+                                                i32, vp]
     L.exe_op_argmax.argtypes = [vp, vp, i32, i32, vp]
     L.exe_rel_bucket.argtypes = [i32, i32, i32, i32]
     L.exe_last_error.restype = C.c_char_p
@@ -343,6 +345,13 @@ def exe_op_decode_attention(dtype, B, q, q_stride, kv, k_offset, cap, length, qp
     _check(lib().exe_op_decode_attention(_stream_ptr(stream), dtype, B, _dev(q), q_stride, _dev(kv), _dev(k_offset),
                                          _dev(cap), _dev(length), _dev(qpos), H, dh, scale, _dev(bias_by_dist),
                                          bias_radius, _dev(out)))
+
+
+def exe_op_decode_attention_paged(dtype, B, q, q_stride, kv_blocks, block_table, max_blocks, block_size, length, qpos, H,
+                                  dh, scale, bias_by_dist, bias_radius, new_kv_offset, out, stream=None):
+    _check(lib().exe_op_decode_attention_paged(_stream_ptr(stream), dtype, B, _dev(q), q_stride, _dev(kv_blocks),
+                                               _dev(block_table), max_blocks, block_size, _dev(length), _dev(qpos), H, dh,
+                                               scale, _dev(bias_by_dist), bias_radius, new_kv_offset, _dev(out)))
 
 
 def exe_op_argmax(logits, rows, n, out, stream=None):

@@ -54,6 +54,20 @@ struct AttnCacheArgs {       // one query row per batch entry against that seque
 };
 hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s);
 
+struct AttnPagedArgs {       // as AttnCacheArgs, with the cache of one layer held in blocks of 2^block_shift positions
+    int dtype, B, H, dh;
+    const void* q; int q_stride;
+    const void* pool;                      // block b at pool + b * 2*H*2^block_shift*dh elements: [K|V][head][row][dh]
+    const int32_t* block_table; int max_blocks; int block_shift;    // [B, max_blocks]
+    const int32_t* len; const int32_t* qpos;
+    float scale;
+    const float* bias_by_dist; int bias_radius;
+    void* out;
+    int new_k_off = 0, new_v_off = 0;      // fused append, as in AttnCacheArgs
+    int mean_len = 0;
+};
+hipError_t launch_attn_paged(const AttnPagedArgs& a, hipStream_t s);
+
 struct AttnPackedArgs {      // ragged prefill over packed qkv [T, 3*H*dh]
     int dtype, T, H, dh, n_seqs;
     const void* qkv;

@@ -49,13 +49,19 @@ template <bool STREAM, typename T> __device__ __forceinline__ uint4 load_chunk(c
     return *(const uint4*)p;
 }
 
-template <typename T, int DH, bool PACKED, int NWV = 4, int U = 4>
+// PAGED (with PACKED = false): the cache of a sequence is a list of blocks of 2^block_shift positions instead of
+// one extent.  Block b of the pool holds [K|V][head][position in block][DH]; block_table[r * max_blocks + i] is the
+// block with positions i * 2^block_shift .. of sequence r.  A wave's rows of one step (RPW * U = 8) never straddle
+// a block (block_shift >= 3), so one table look-up per wave and step suffices.
+template <typename T, int DH, bool PACKED, int NWV = 4, int U = 4, bool PAGED = false>
 __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
     const T* __restrict__ q, int q_stride, const T* kvbuf, const int64_t* __restrict__ base,
     const int32_t* __restrict__ cap, const int32_t* __restrict__ len, const int32_t* __restrict__ qpos_arr,
     const int32_t* __restrict__ tok_b, const int32_t* __restrict__ cu, int layer, int H, int causal, float scale,
-    const float* __restrict__ bias_by_dist, int radius, T* __restrict__ out, int new_k_off, int new_v_off)
+    const float* __restrict__ bias_by_dist, int radius, T* __restrict__ out, int new_k_off, int new_v_off,
+    const int32_t* __restrict__ block_table = nullptr, int max_blocks = 0, int block_shift = 0)
 {
+    static_assert(!(PAGED && PACKED), "paged mode is a cache mode");
     constexpr int EPL = 16 / sizeof(T);      // elements per 16-byte chunk
     constexpr int LPR = DH / EPL;            // lanes that share one key/value row
     constexpr int RPW = 64 / LPR;            // rows per wave per load
@@ -80,6 +86,12 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
         kp = kvbuf + (int64_t)t0 * row_stride + inner + h * DH;
         vp = kp + inner;
         qp = kvbuf + (int64_t)r * row_stride + h * DH;
+    } else if (PAGED) {
+        nk = len[r];
+        qpos = qpos_arr[r];
+        row_stride = DH;
+        kp = vp = kvbuf;                    // set per block below
+        qp = q + (int64_t)r * q_stride + h * DH;
     } else {
         int64_t c = cap[r];
         nk = len[r];
@@ -89,6 +101,10 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
         vp = kp + (int64_t)H * c * DH;
         qp = q + (int64_t)r * q_stride + h * DH;
     }
+    // PAGED: keys of block b for this head start at block_k(b), its values H * block_rows * DH elements further on
+    const int block_rows = 1 << block_shift;
+    const int32_t* tbl = PAGED ? block_table + (int64_t)r * max_blocks : nullptr;
+    auto block_k = [&](int b) { return kvbuf + ((int64_t)b * 2 * H + h) * block_rows * DH; };
     // Fused append: the newest position's key/value rows come from the projection output; one 16-lane group
     // stores them into the cache, and every lane that meets row nk-1 reads it from the source instead of the
     // cache, so no ordering between that store and the loads is needed.
@@ -97,8 +113,15 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
         knew = qp + new_k_off;
         vnew = qp + new_v_off;
         if (wave == 0 && rg == 0) {
-            *(uint4*)(const_cast<T*>(kp) + (int64_t)(nk - 1) * DH + cl * EPL) = *(const uint4*)(knew + cl * EPL);
-            *(uint4*)(const_cast<T*>(vp) + (int64_t)(nk - 1) * DH + cl * EPL) = *(const uint4*)(vnew + cl * EPL);
+            const T *kd = kp, *vd = vp;
+            int row = nk - 1;
+            if (PAGED) {
+                kd = block_k(tbl[row >> block_shift]);
+                vd = kd + (int64_t)H * block_rows * DH;
+                row &= block_rows - 1;
+            }
+            *(uint4*)(const_cast<T*>(kd) + (int64_t)row * DH + cl * EPL) = *(const uint4*)(knew + cl * EPL);
+            *(uint4*)(const_cast<T*>(vd) + (int64_t)row * DH + cl * EPL) = *(const uint4*)(vnew + cl * EPL);
         }
     }
 
@@ -120,10 +143,16 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
     for (int j0 = wave * RPW * U; j0 < nc; j0 += NWV * RPW * U) {
         uint4 kc[U], vc[U];
         float s[U];
+        int jb = 0;                           // PAGED: first row of the block that holds rows j0 .. j0 + RPW*U - 1
+        if (PAGED) {
+            kp = block_k(tbl[j0 >> block_shift]);
+            vp = kp + (int64_t)H * block_rows * DH;
+            jb = j0 & ~(block_rows - 1);
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int j = j0 + u * RPW + rg;
-            int jj = j < nc ? j : nc - 1;
+            int jj = (j < nc ? j : nc - 1) - jb;
             kc[u] = load_chunk<!PACKED>(kp + (int64_t)jj * row_stride + cl * EPL);
             vc[u] = load_chunk<!PACKED>(vp + (int64_t)jj * row_stride + cl * EPL);
         }
@@ -224,6 +253,32 @@ hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s)
     do {                                                                                                        \
         if (nwv == 4) EXE_ROW_N(T, DH, 4);                                                                      \
         else EXE_ROW_N(T, DH, 16);                                                                              \
+    } while (0)
+    if (a.dtype == DT_F32 && a.dh == 64) EXE_ROW(float, 64);
+    else if (a.dtype == DT_F32 && a.dh == 128) EXE_ROW(float, 128);
+    else if (a.dtype == DT_BF16 && a.dh == 64) EXE_ROW(bf16_t, 64);
+    else if (a.dtype == DT_BF16 && a.dh == 128) EXE_ROW(bf16_t, 128);
+    else return hipErrorInvalidValue;
+#undef EXE_ROW
+#undef EXE_ROW_N
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_paged(const AttnPagedArgs& a, hipStream_t s)
+{
+    if (a.B <= 0) return hipSuccess;
+    if (a.block_shift < 3 || a.block_shift > 12 || a.max_blocks < 1) return hipErrorInvalidValue;
+    dim3 grid(a.H, a.B);
+    int nwv = a.mean_len > 0 && a.mean_len <= ATTN_SHORT_LEN ? 4 : 16;
+#define EXE_ROW_N(T, DH, NWV)                                                                                       \
+    attn_row_kernel<T, DH, false, NWV, 2, true><<<grid, NWV * 64, 0, s>>>(                                          \
+        (const T*)a.q, a.q_stride, (const T*)a.pool, nullptr, nullptr, a.len, a.qpos, nullptr, nullptr, 0, a.H, 0,  \
+        a.scale, a.bias_by_dist, a.bias_radius, (T*)a.out, a.new_k_off, a.new_v_off, a.block_table, a.max_blocks,   \
+        a.block_shift)
+#define EXE_ROW(T, DH)                                                                                              \
+    do {                                                                                                            \
+        if (nwv == 4) EXE_ROW_N(T, DH, 4);                                                                          \
+        else EXE_ROW_N(T, DH, 16);                                                                                  \
     } while (0)
     if (a.dtype == DT_F32 && a.dh == 64) EXE_ROW(float, 64);
     else if (a.dtype == DT_F32 && a.dh == 128) EXE_ROW(float, 128);

@@ -1529,6 +1529,29 @@ extern "C" int exe_op_decode_attention(void* hip_stream, int32_t dtype, int32_t 
     return EXE_OK;
 }
 
+extern "C" int exe_op_decode_attention_paged(void* hip_stream, int32_t dtype, int32_t B, const void* q, int32_t q_stride,
+                                             const void* kv_blocks, const int32_t* block_table, int32_t max_blocks,
+                                             int32_t block_size, const int32_t* len, const int32_t* qpos, int32_t H,
+                                             int32_t dh, float scale, const float* bias_by_dist, int32_t bias_radius,
+                                             int32_t new_kv_offset, void* out)
+{
+    if (B < 0 || !q || !kv_blocks || !block_table || !len || !qpos || !out || H < 1 || max_blocks < 1)
+        return fail(EXE_ERR_ARG, "bad paged decode attention arguments");
+    if (dh != 64 && dh != 128) return fail(EXE_ERR_SHAPE, "head_dim must be 64 or 128");
+    int shift = 0;
+    while ((1 << shift) < block_size) ++shift;
+    if (block_size < 8 || block_size > 4096 || (1 << shift) != block_size)
+        return fail(EXE_ERR_ARG, "block_size %d is not a power of two in [8, 4096]", block_size);
+    AttnPagedArgs a{dtype, B, H, dh, q, q_stride, kv_blocks, block_table, max_blocks, shift, len, qpos, scale, bias_by_dist,
+                    bias_radius, out};
+    if (new_kv_offset > 0) {
+        a.new_k_off = new_kv_offset;
+        a.new_v_off = 2 * new_kv_offset;
+    }
+    HIP_TRY(launch_attn_paged(a, (hipStream_t)hip_stream));
+    return EXE_OK;
+}
+
 extern "C" int exe_op_argmax(void* hip_stream, const float* logits, int32_t rows, int32_t n, int32_t* out)
 {
     if (!logits || !out || rows < 0 || n < 1) return fail(EXE_ERR_ARG, "bad argmax arguments");

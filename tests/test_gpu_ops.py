@@ -200,6 +200,89 @@ def test_decode_attention(dtype, dh, H, use_bias):
     assert worst < (1e-5 if dtype == F32 else 2.0 ** -7), worst
 
 
+@pytest.mark.parametrize("dtype,dh,H", [(BF16, 128, 5), (F32, 64, 3)])
+@pytest.mark.parametrize("block_size", [8, 64, 256])
+@pytest.mark.parametrize("fused_append", [0, 1])
+def test_decode_attention_paged(dtype, dh, H, block_size, fused_append):
+    """Block-table variant: the same rows scattered over shuffled blocks give the extent kernel's result bit for
+    bit (same arithmetic in the same order) and the oracle's within tolerance; with the fused append the newest row
+    comes from the projection output and lands in the right block."""
+    # (Section 2 of the paper mentions paging of the key/value cache; the oracle is the plain attention definition)
+    td = torch.float32 if dtype == F32 else torch.bfloat16
+    lens = [1, 8, 9, 63, 64, 65, 300, 1023, 17]
+    B = len(lens)
+    inner = H * dh
+    nblk = [(L + block_size - 1) // block_size for L in lens]
+    max_blocks = max(nblk) + 1
+    total = sum(nblk) + 3                                   # a few blocks nobody owns
+    perm = np.random.default_rng(41).permutation(total)
+    table = np.full((B, max_blocks), -1, dtype=np.int32)    # unused entries must never be read
+    nxt = 0
+    for b in range(B):
+        for i in range(nblk[b]):
+            table[b, i] = perm[nxt]
+            nxt += 1
+    table[table < 0] = 0
+    blk_elems = 2 * H * block_size * dh
+    # per-sequence contiguous K/V [H][L][dh], the ground truth for both layouts
+    Ks = [rnd((H, L, dh), 50 + b, 1.0, td) for b, L in enumerate(lens)]
+    Vs = [rnd((H, L, dh), 70 + b, 1.0, td) for b, L in enumerate(lens)]
+    qkv = rnd((B, 3 * inner), 15, 1.0, td)                  # q, then the newest key and value rows when fused
+    pool = torch.zeros(total * blk_elems, dtype=td)
+    pv = pool.view(total, 2, H, block_size, dh)
+    for b, L in enumerate(lens):
+        if fused_append:                                   # the newest row is what the projection produced
+            Ks[b][:, L - 1, :] = qkv[b, inner:2 * inner].view(H, dh)
+            Vs[b][:, L - 1, :] = qkv[b, 2 * inner:].view(H, dh)
+        in_cache = L - 1 if fused_append else L
+        for p in range(in_cache):
+            blk = table[b, p // block_size]
+            pv[blk, 0, :, p % block_size, :] = Ks[b][:, p, :]
+            pv[blk, 1, :, p % block_size, :] = Vs[b][:, p, :]
+    qpos = [L - 1 for L in lens]
+    scale = 1.0 / np.sqrt(dh)
+    i32 = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=DEV)
+    pool_d = pool.to(DEV)
+    out = torch.zeros((B, inner), dtype=td, device=DEV)
+    exe.exe_op_decode_attention_paged(dtype, B, qkv.to(DEV), 3 * inner, pool_d, i32(table), max_blocks, block_size, i32(lens),
+                                      i32(qpos), H, dh, scale, None, 0, inner if fused_append else 0, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    # the extent kernel on the same rows
+    caps = [((L + 7) // 8) * 8 for L in lens]
+    offs, tot = [], 0
+    for c in caps:
+        offs.append(tot)
+        tot += 2 * H * c * dh
+    ext = torch.zeros(tot, dtype=td)
+    for b, L in enumerate(lens):
+        e = ext[offs[b]: offs[b] + 2 * H * caps[b] * dh].view(2, H, caps[b], dh)
+        e[0, :, :L, :] = Ks[b]
+        e[1, :, :L, :] = Vs[b]
+    out2 = torch.zeros((B, inner), dtype=td, device=DEV)
+    i64 = lambda a: torch.tensor(a, dtype=torch.int64, device=DEV)
+    exe.exe_op_decode_attention(dtype, B, qkv.to(DEV), 3 * inner, ext.to(DEV), i64(offs), i32(caps), i32(lens), i32(qpos), H, dh,
+                                scale, None, 0, out2)
+    torch.cuda.synchronize()
+    if not fused_append:                                   # (the fused append folds the newest row in last: another order)
+        assert torch.equal(out, out2)
+    else:
+        assert relerr(got, out2.float().cpu().numpy()) < (1e-5 if dtype == F32 else 2.0 ** -7)
+    if fused_append:                                       # the newest rows were stored where the table says
+        back = pool_d.cpu().view(total, 2, H, block_size, dh)
+        for b, L in enumerate(lens):
+            blk, row = table[b, (L - 1) // block_size], (L - 1) % block_size
+            assert torch.equal(back[blk, 0, :, row, :], Ks[b][:, L - 1, :]) and torch.equal(back[blk, 1, :, row, :], Vs[b][:, L - 1, :])
+    worst = 0.0
+    qf = qkv.float().numpy()
+    for b, L in enumerate(lens):
+        for h in range(H):
+            ref = oracle_attention(qf[b, h * dh:(h + 1) * dh], Ks[b][h].float().numpy(), Vs[b][h].float().numpy(),
+                                   float(np.float32(scale)), None)
+            worst = max(worst, relerr(got[b, h * dh:(h + 1) * dh], ref))
+    assert worst < (1e-5 if dtype == F32 else 2.0 ** -7), worst
+
+
 @pytest.mark.parametrize("dtype,dh,H,generic", [(BF16, 128, 3, 0), (BF16, 128, 3, 1), (BF16, 64, 2, 0), (F32, 64, 4, 0)])
 @pytest.mark.parametrize("causal,use_bias", [(1, 0), (0, 1), (1, 1), (0, 0)])
 def test_prefill_attention(dtype, dh, H, generic, causal, use_bias):
