@@ -175,6 +175,9 @@ def main():
     ap.add_argument("--rra", type=int, default=0, metavar="N_D",
                     help="also run the refilled (RRA) schedule: 3 x B0 requests, decode batch B0, N_D decode iterations "
                          "between encoding phases (secondary figures under the key \"rra\")")
+    ap.add_argument("--kv-block", type=int, default=0, metavar="POSITIONS",
+                    help="paged K/V pool with blocks of this many positions (default 0: one extent per sequence, the "
+                         "configuration the headline is measured in)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -218,7 +221,8 @@ def main():
     if args.rra:
         need_tokens = int(need_tokens * 1.3)          # refilled batches fragment the pool: leave slack
     cfg = exe.config_from_shape(shape, kv_pool_bytes=need_tokens * kv_tok, max_seqs=job.n,
-                                max_batch_tokens=job.encode_batch * max_in, max_batch_seqs=max(job.n, job.encode_batch))
+                                max_batch_tokens=job.encode_batch * max_in, max_batch_seqs=max(job.n, job.encode_batch),
+                                kv_block_size=args.kv_block)
     stream = torch.cuda.Stream()
     m = exe.Model(cfg, weights, stream=stream)
     print(f"[bench] K/V pool {need_tokens * kv_tok / 1e9:.1f} GB for {job.n} sequences, {need_tokens} positions",
@@ -255,7 +259,8 @@ def main():
         "config": {"workload": WORKLOADS[args.workload].format(L=shape.n_layers, LD=shape.n_dec_layers,
                                                                nb=-(-job.n // job.encode_batch), eb=job.encode_batch, n=job.n),
                    "decode_batch": job.n, "encode_batch": job.encode_batch, "input_tokens": n_in,
-                   "generated_tokens": n_gen, "decode_iterations": n_steps, "layers": shape.n_layers + shape.n_dec_layers},
+                   "generated_tokens": n_gen, "decode_iterations": n_steps, "layers": shape.n_layers + shape.n_dec_layers,
+                   "kv_block_size": args.kv_block},
         "encode_tokens_per_s": round(K * n_in / t_enc, 1),
         "decode_tokens_per_s": round(K * n_dec_tokens / t_dec, 1),
         "encode_s_per_step": round(t_enc / K, 4), "decode_s_per_step": round(t_dec / K, 4),

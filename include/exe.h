@@ -68,6 +68,11 @@ typedef struct exe_config {
     int32_t max_seqs;        /* sequence ids are 0 .. max_seqs-1 */
     int32_t max_batch_tokens;/* largest sum of input lengths in one exe_encode (workspace size) */
     int32_t max_batch_seqs;  /* largest number of sequences in one exe_encode / exe_decode_step call */
+    int32_t kv_block_size;   /* 0: every sequence's K/V entries live in one extent of the pool with a reserved capacity.
+                              * A power of two in [8, 4096]: paged pool (Section 2: paging applied to the memorization
+                              * cache) -- the pool is cut into blocks of that many positions, a sequence takes blocks as
+                              * it grows (reserve_lengths are then only validated), none is wasted on capacity not yet
+                              * used.  Decoder-only models only (else EXE_ERR_UNIMPLEMENTED). */
 } exe_config_t;
 
 /* A weight tensor: device pointer, dtype = config.dtype. */

@@ -33,7 +33,7 @@ class Config(C.Structure):
                  "max_pos", "act", "norm", "pos", "rel_buckets", "rel_max_dist", "cross_rel_bias", "dtype",
                  "has_embed", "has_lm_head", "scale_mode")] + \
                [("norm_eps", C.c_float), ("kv_pool_bytes", C.c_uint64), ("max_seqs", C.c_int32),
-                ("max_batch_tokens", C.c_int32), ("max_batch_seqs", C.c_int32)]
+                ("max_batch_tokens", C.c_int32), ("max_batch_seqs", C.c_int32), ("kv_block_size", C.c_int32)]
 
 
 class Tensor(C.Structure):
@@ -190,12 +190,13 @@ def _stream_ptr(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
-def config_from_shape(shape, kv_pool_bytes: int, max_seqs: int, max_batch_tokens: int, max_batch_seqs: int) -> Config:
+def config_from_shape(shape, kv_pool_bytes: int, max_seqs: int, max_batch_tokens: int, max_batch_seqs: int,
+                      kv_block_size: int = 0) -> Config:
     """`shape` is any object with the ModelShape fields of the workload module."""
     return Config(shape.arch, shape.n_layers, shape.n_dec_layers, shape.d_model, shape.n_heads, shape.head_dim,
                   shape.d_ff, shape.vocab, shape.max_pos, shape.act, shape.norm, shape.pos, shape.rel_buckets,
                   shape.rel_max_dist, shape.cross_rel_bias, shape.dtype, shape.has_embed, shape.has_lm_head,
-                  shape.scale_mode, shape.norm_eps, kv_pool_bytes, max_seqs, max_batch_tokens, max_batch_seqs)
+                  shape.scale_mode, shape.norm_eps, kv_pool_bytes, max_seqs, max_batch_tokens, max_batch_seqs, kv_block_size)
 
 
 def exe_version() -> str:

@@ -35,6 +35,9 @@ hipError_t launch_norm(int dtype, int rms, const float* x, const int32_t* row_in
 hipError_t launch_kv_append(int dtype, const void* src, int ld, int k_off, int v_off, int T, const int32_t* tok_b,
                             const int32_t* tok_pos, const int64_t* base, const int32_t* cap, int layer, int H, int dh,
                             void* pool, hipStream_t s);
+hipError_t launch_kv_append_paged(int dtype, const void* src, int ld, int k_off, int v_off, int T, const int32_t* tok_b,
+                                  const int32_t* tok_pos, const int32_t* table, int table_w, int shift, int H, int dh,
+                                  void* layer_pool, hipStream_t s);
 hipError_t launch_argmax(const float* logits, int rows, int n, int32_t* out, hipStream_t s);
 
 struct AttnCacheArgs {       // one query row per batch entry against that sequence's cached K/V

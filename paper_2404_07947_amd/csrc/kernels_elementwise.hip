@@ -179,6 +179,46 @@ hipError_t launch_kv_append(int dtype, const void* src, int ld, int k_off, int v
     return hipGetLastError();
 }
 
+// Paged pool: the same rows into blocks of 2^shift positions.  `layer_pool` is the layer's slab of blocks, block b at
+// b * 2*H*2^shift*dh elements holding [K|V][head][row][dh]; table [sequences][table_w] lists each sequence's blocks.
+template <typename T>
+__global__ void kv_append_paged_kernel(const T* __restrict__ src, int ld, int k_off, int v_off,
+                                       const int32_t* __restrict__ tok_b, const int32_t* __restrict__ tok_pos,
+                                       const int32_t* __restrict__ table, int table_w, int shift, int H, int dh,
+                                       T* __restrict__ layer_pool)
+{
+    constexpr int EPL = 16 / sizeof(T);
+    int t = blockIdx.x, kv = blockIdx.y;
+    int b = tok_b ? tok_b[t] : t;
+    int pos = tok_pos[t];
+    int64_t rows = (int64_t)1 << shift;
+    int blk = table[(int64_t)b * table_w + (pos >> shift)];
+    const T* s = src + (int64_t)t * ld + (kv ? v_off : k_off);
+    T* dst = layer_pool + ((int64_t)blk * 2 + kv) * H * rows * dh + (int64_t)(pos & (rows - 1)) * dh;
+    int inner = H * dh;
+    for (int e = threadIdx.x * EPL; e < inner; e += blockDim.x * EPL) {
+        int head = e / dh, col = e - head * dh;
+        *(uint4*)(dst + (int64_t)head * rows * dh + col) = *(const uint4*)(s + e);
+    }
+}
+
+hipError_t launch_kv_append_paged(int dtype, const void* src, int ld, int k_off, int v_off, int T, const int32_t* tok_b,
+                                  const int32_t* tok_pos, const int32_t* table, int table_w, int shift, int H, int dh,
+                                  void* layer_pool, hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    int epl = dtype == DT_F32 ? 4 : 8;
+    if (dh % epl || ld % epl || k_off % epl || v_off % epl || !table || table_w < 1) return hipErrorInvalidValue;
+    dim3 grid(T, 2);
+    if (dtype == DT_F32)
+        kv_append_paged_kernel<float><<<grid, 256, 0, s>>>((const float*)src, ld, k_off, v_off, tok_b, tok_pos, table, table_w,
+                                                           shift, H, dh, (float*)layer_pool);
+    else
+        kv_append_paged_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)src, ld, k_off, v_off, tok_b, tok_pos, table,
+                                                            table_w, shift, H, dh, (bf16_t*)layer_pool);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- greedy argmax
 // One workgroup per row; ties resolve to the lowest index at every level of the reduction.
 __global__ void argmax_kernel(const float* __restrict__ logits, int n, int32_t* __restrict__ out)

@@ -128,6 +128,7 @@ struct Seq {
     int64_t base = -1, elems = 0;
     int n_in = 0;            // enc-dec: encoder length = cross K/V length
     int64_t xbase = -1, xelems = 0;
+    std::vector<int32_t> blocks;   // paged pool: the sequence's blocks in position order (cap = blocks * block rows)
 };
 
 struct DecLayerW {   // decoder-only layer, or the shared part of T5 layers
@@ -166,6 +167,12 @@ struct exe_model {
     Pool pool;
     std::vector<Seq> seqs;
     int live = 0;
+    // paged pool (cfg.kv_block_size > 0): per decoder layer a slab of n_blocks blocks, block b of layer l at element
+    // (l * n_blocks + b) * blk_elems, each [K|V][head][blk_rows][head_dim]; a sequence owns the same block ids in
+    // every layer.  The extent allocator above then serves exe_profile only (which needs an empty pool).
+    int blk_rows = 0, blk_shift = 0, n_blocks = 0;
+    int64_t blk_elems = 0;
+    std::vector<int32_t> free_blocks;      // stack; the back is handed out next
 
     // activation workspace
     int rows_cap = 0;
@@ -394,6 +401,29 @@ extern "C" int exe_model_load(const exe_config_t* cfg, const exe_tensor_t* weigh
     m->pool.reset(m->pool.elems);
     m->seqs.resize(c.max_seqs);
     m->mark.assign(c.max_seqs, 0);
+    size_t table_max = 0;                  // ints of the widest block table one call can stage
+    if (c.kv_block_size != 0) {
+        int sh = 0;
+        while ((1 << sh) < c.kv_block_size) ++sh;
+        if (c.kv_block_size < 8 || c.kv_block_size > 4096 || (1 << sh) != c.kv_block_size) {
+            free_model(m);
+            return fail(EXE_ERR_ARG, "kv_block_size %d is not a power of two in [8, 4096]", c.kv_block_size);
+        }
+        if (c.arch != EXE_ARCH_DECODER_ONLY) {
+            free_model(m);
+            return fail(EXE_ERR_UNIMPLEMENTED, "the paged K/V pool serves decoder-only models");
+        }
+        m->blk_rows = c.kv_block_size;
+        m->blk_shift = sh;
+        m->blk_elems = (int64_t)2 * m->inner * m->blk_rows;
+        int64_t nb = m->pool.elems / ((int64_t)n_dec_layers(c) * m->blk_elems);
+        m->n_blocks = (int)std::min<int64_t>(nb, 1 << 24);
+        m->free_blocks.resize(m->n_blocks);
+        for (int b = 0; b < m->n_blocks; ++b) m->free_blocks[b] = m->n_blocks - 1 - b;     // block 0 goes out first
+        bool learned = c.has_embed && c.pos == EXE_POS_LEARNED;
+        size_t width = learned ? (size_t)((c.max_pos + m->blk_rows - 1) >> sh) : (size_t)m->n_blocks;
+        table_max = (size_t)c.max_batch_seqs * std::max<size_t>(width, 1);
+    }
 
     int rows = std::max(c.max_batch_tokens, c.max_batch_seqs);
     m->rows_cap = rows;
@@ -425,7 +455,8 @@ extern "C" int exe_model_load(const exe_config_t* cfg, const exe_tensor_t* weigh
     // descriptor staging: token-sized int arrays (3), tile list (2 ints per 128 query rows + one per sequence),
     // and per-sequence arrays (int64 x2, int32 x6)
     size_t tiles_max = (size_t)c.max_batch_tokens / PREFILL_TILE_Q + c.max_batch_seqs + 1;
-    m->stage_bytes = 3 * (size_t)rows * 4 + tiles_max * 8 + (size_t)(c.max_batch_seqs + 1) * (2 * 8 + 6 * 4) + 256;
+    m->stage_bytes = 3 * (size_t)rows * 4 + tiles_max * 8 + (size_t)(c.max_batch_seqs + 1) * (2 * 8 + 6 * 4) + 256 +
+                     table_max * 4 + 16;
     LOAD_TRY(hipHostMalloc((void**)&m->stage_h, m->stage_bytes, hipHostMallocDefault));
     LOAD_TRY(hipMalloc((void**)&m->stage_d, m->stage_bytes));
 #undef LOAD_TRY
@@ -513,6 +544,7 @@ static int run_head(exe_model* m, const int32_t* row_index_dev, int n, int32_t* 
 
 static void release_seq(exe_model* m, Seq& s)
 {
+    for (auto it = s.blocks.rbegin(); it != s.blocks.rend(); ++it) m->free_blocks.push_back(*it);
     if (s.base >= 0) m->pool.release(s.base, s.elems);
     if (s.xbase >= 0) m->pool.release(s.xbase, s.xelems);
     if (s.live) m->live--;
@@ -520,12 +552,40 @@ static void release_seq(exe_model* m, Seq& s)
 }
 
 static int round8(int x) { return (x + 7) & ~7; }
+static bool paged(const exe_model* m) { return m->blk_rows > 0; }
+static int blocks_for(const exe_model* m, int positions) { return (positions + m->blk_rows - 1) >> m->blk_shift; }
+static void* layer_blocks(const exe_model* m, int layer)
+{
+    return (char*)m->pool.ptr + (size_t)layer * m->n_blocks * m->blk_elems * m->esz;
+}
+// takes `count` blocks for `s` (the caller has checked that they are free)
+static void take_blocks(exe_model* m, Seq& s, int count)
+{
+    for (int i = 0; i < count; ++i) {
+        s.blocks.push_back(m->free_blocks.back());
+        m->free_blocks.pop_back();
+    }
+    s.cap = (int)s.blocks.size() * m->blk_rows;
+}
+// widest block list among `seqs`, and the table [n][width] staged for the device
+static int stage_block_table(exe_model* m, Stager& st, const std::vector<const Seq*>& seqs, int32_t** dev)
+{
+    size_t w = 1;
+    for (const Seq* s : seqs) w = std::max(w, s->blocks.size());
+    int32_t* h = st.take<int32_t>(seqs.size() * w, dev);
+    if (st.off > m->stage_bytes) return (int)w;       // the caller reports the overflow; nothing is written
+    for (size_t i = 0; i < seqs.size(); ++i)
+        for (size_t j = 0; j < w; ++j) h[i * w + j] = j < seqs[i]->blocks.size() ? seqs[i]->blocks[j] : 0;
+    return (int)w;
+}
 
 // ---------------------------------------------------------------- encode
 struct EncodeDesc {
     int32_t *tok, *tok_b, *tok_pos, *cu, *cap, *last, *tiles, *xcap;
     int64_t *base, *xbase;
     int n_tiles;
+    int32_t* table = nullptr;   // paged pool: block table [n][table_w]
+    int table_w = 0;
 };
 
 // One encode (prefill) layer over T packed tokens of n sequences.  parts: bit 0 = everything but the
@@ -539,7 +599,12 @@ static int encode_layer(exe_model* m, const DecLayerW& L, int layer, int n, int 
     if (parts & 1) {
         if ((r = run_norm(m, nullptr, T, L.n1_g, L.n1_b, 1.f, m->a))) return r;
         if ((r = run_gemm(m, T, 3 * m->inner, c.d_model, m->a, L.w_qkv, L.b_qkv, -1, 1.f, OUT_T, m->qkv))) return r;
-        if (!encdec)
+        if (!encdec && d.table)
+            LAUNCH(m, EXE_K_OTHER, 4.0 * T * m->inner * esz_of(m), 0.0,
+                   launch_kv_append_paged(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, T, d.tok_b, d.tok_pos,
+                                          d.table, d.table_w, m->blk_shift, c.n_heads, c.head_dim, layer_blocks(m, layer),
+                                          m->stream));
+        else if (!encdec)
             LAUNCH(m, EXE_K_OTHER, 4.0 * T * m->inner * esz_of(m), 0.0,
                    launch_kv_append(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, T, d.tok_b, d.tok_pos, d.base,
                                     d.cap, layer, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
@@ -658,11 +723,20 @@ extern "C" int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, con
         for (int t = 0; t < T; ++t)
             if (tokens_packed[t] < 0 || tokens_packed[t] >= c.vocab) return fail(EXE_ERR_ARG, "token %d out of range", tokens_packed[t]);
 
-    // admit: allocate every extent or none
+    // admit: allocate every extent (paged pool: every block) or none
     int ndl = n_dec_layers(c);
     std::vector<Seq> fresh(n);
     bool ok = true;
-    for (int i = 0; i < n && ok; ++i) {
+    if (paged(m)) {
+        // blocks for the input positions only; decode steps take further blocks as the sequences grow
+        int64_t need = 0;
+        for (int i = 0; i < n; ++i) need += blocks_for(m, lens[i]);
+        if (need > (int64_t)m->free_blocks.size())
+            return fail(EXE_ERR_OOM_KV, "K/V pool exhausted (%lld blocks needed, %lld of %d free)", (long long)need,
+                        (long long)m->free_blocks.size(), m->n_blocks);
+        for (int i = 0; i < n; ++i) take_blocks(m, fresh[i], blocks_for(m, lens[i]));
+    }
+    for (int i = 0; i < n && ok && !paged(m); ++i) {
         Seq& s = fresh[i];
         s.cap = caps[i];
         s.elems = (int64_t)ndl * 2 * m->inner * s.cap;
@@ -677,6 +751,8 @@ extern "C" int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, con
     }
     auto rollback = [&]() {
         for (auto& s : fresh) {
+            for (auto it = s.blocks.rbegin(); it != s.blocks.rend(); ++it) m->free_blocks.push_back(*it);
+            s.blocks.clear();
             if (s.base >= 0) m->pool.release(s.base, s.elems);
             if (s.xbase >= 0) m->pool.release(s.xbase, s.xelems);
         }
@@ -687,6 +763,11 @@ extern "C" int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, con
     Stager st{m};
     EncodeDesc d{};
     fill_encode_desc(m, st, d, n, lens, c.has_embed ? tokens_packed : nullptr, fresh);
+    if (paged(m)) {
+        std::vector<const Seq*> sp(n);
+        for (int i = 0; i < n; ++i) sp[i] = &fresh[i];
+        d.table_w = stage_block_table(m, st, sp, &d.table);
+    }
     if (st.off > m->stage_bytes) { rollback(); return fail(EXE_ERR_ARG, "descriptor staging overflow"); }
 
     auto body = [&]() -> int {
@@ -739,6 +820,8 @@ struct DecodeDesc {
     int64_t *base, *xbase;
     double self_bytes, self_flops, x_bytes, x_flops;
     int mean_len, mean_xlen;      // average self / cross rows per sequence
+    int32_t* table = nullptr;     // paged pool: block table [n][table_w]
+    int table_w = 0;
 };
 
 static void fill_decode_desc(exe_model* m, Stager& st, DecodeDesc& d, const std::vector<DecodeSeq>& ds)
@@ -803,7 +886,14 @@ static int decode_layer(exe_model* m, const DecLayerW& L, int layer, int n, cons
                    launch_kv_append(c.dtype, m->qkv, 3 * m->inner, m->inner, 2 * m->inner, n, nullptr, d.pos, d.base, d.cap,
                                     layer, c.n_heads, c.head_dim, m->pool.ptr, m->stream));
     }
-    if (parts & 2) {
+    if ((parts & 2) && d.table) {
+        AttnPagedArgs a{c.dtype, n, c.n_heads, c.head_dim, m->qkv, 3 * m->inner, layer_blocks(m, layer), d.table, d.table_w,
+                        m->blk_shift, d.len, d.pos, attn_scale(m), nullptr, 0, m->ctx};
+        a.new_k_off = m->inner;
+        a.new_v_off = 2 * m->inner;
+        a.mean_len = d.mean_len;
+        LAUNCH(m, EXE_K_DECODE_ATTN, d.self_bytes, d.self_flops, launch_attn_paged(a, m->stream));
+    } else if (parts & 2) {
         AttnCacheArgs a{c.dtype, n, c.n_heads, c.head_dim, m->qkv, 3 * m->inner, m->pool.ptr, d.base, d.cap, d.len, d.pos,
                         layer, attn_scale(m), encdec ? m->bias_dec : nullptr, m->radius, m->ctx};
         a.new_k_off = m->inner;
@@ -841,6 +931,7 @@ extern "C" int exe_decode_step(exe_model_t* m, int32_t n, const int32_t* seq_ids
     if (n > c.max_batch_seqs) return fail(EXE_ERR_ARG, "n = %d exceeds max_batch_seqs = %d", n, c.max_batch_seqs);
     if (c.has_embed ? !tokens_in : !hidden_in) return fail(EXE_ERR_ARG, "missing tokens_in / hidden_in");
     bool learned = c.has_embed && c.pos == EXE_POS_LEARNED;
+    int64_t blocks_needed = 0;
     ++m->mark_gen;
     for (int i = 0; i < n; ++i) {
         int id = seq_ids[i];
@@ -849,7 +940,12 @@ extern "C" int exe_decode_step(exe_model_t* m, int32_t n, const int32_t* seq_ids
         m->mark[id] = m->mark_gen;
         const Seq& s = m->seqs[id];
         if (kv_lengths[i] != s.len + 1) return fail(EXE_ERR_BAD_LENGTH, "seq %d: kv_length %d, expected %d", id, kv_lengths[i], s.len + 1);
-        if (s.len + 1 > s.cap) return fail(EXE_ERR_OOM_KV, "seq %d: reserved capacity %d exhausted", id, s.cap);
+        if (paged(m)) {
+            if (s.len + 1 > s.cap && ++blocks_needed > (int64_t)m->free_blocks.size())
+                return fail(EXE_ERR_OOM_KV, "K/V pool exhausted: no free block for seq %d (%d blocks in all)", id, m->n_blocks);
+        } else if (s.len + 1 > s.cap) {
+            return fail(EXE_ERR_OOM_KV, "seq %d: reserved capacity %d exhausted", id, s.cap);
+        }
         if (learned && s.len + 1 > c.max_pos) return fail(EXE_ERR_BAD_LENGTH, "seq %d: position %d exceeds max_pos", id, s.len);
         if (c.has_embed && (tokens_in[i] < 0 || tokens_in[i] >= c.vocab)) return fail(EXE_ERR_ARG, "token %d out of range", tokens_in[i]);
     }
@@ -857,10 +953,17 @@ extern "C" int exe_decode_step(exe_model_t* m, int32_t n, const int32_t* seq_ids
     DecodeDesc dd{};
     std::vector<DecodeSeq> ds(n);
     for (int i = 0; i < n; ++i) {
-        const Seq& s = m->seqs[seq_ids[i]];
+        Seq& s = m->seqs[seq_ids[i]];
+        if (paged(m) && s.len + 1 > s.cap) take_blocks(m, s, 1);          // checked above: the blocks are there
         ds[i] = DecodeSeq{c.has_embed ? tokens_in[i] : 0, s.len, s.cap, s.base, s.n_in, s.xbase < 0 ? 0 : s.xbase};
     }
     fill_decode_desc(m, st, dd, ds);
+    if (paged(m)) {
+        std::vector<const Seq*> sp(n);
+        for (int i = 0; i < n; ++i) sp[i] = &m->seqs[seq_ids[i]];
+        dd.table_w = stage_block_table(m, st, sp, &dd.table);
+        if (st.off > m->stage_bytes) return fail(EXE_ERR_ARG, "descriptor staging overflow");
+    }
     HIP_TRY(hipMemcpyAsync(m->stage_d, m->stage_h, st.off, hipMemcpyHostToDevice, m->stream));
     int r;
     if ((r = decode_input(m, dd, n, hidden_in))) return r;
@@ -906,6 +1009,27 @@ extern "C" int exe_seq_length(exe_model_t* m, int32_t seq_id)
 // Exported layout: the self-attention entries [decoder layer][K|V][head][kv_len][head_dim] in the storage type,
 // then (encoder-decoder models) the cross-attention entries [decoder layer][K|V][head][cross_len][head_dim]:
 // the extent without its unused capacity.  Either side of the copy is one strided 2-D transfer.
+// paged pool: the self-attention entries of `s` between its blocks and a host buffer in the exported layout, one
+// strided copy per (layer, block)
+static hipError_t copy_blocks(exe_model* m, const Seq& s, char* host, bool to_host)
+{
+    size_t rowb = (size_t)m->c.head_dim * m->esz, layer_rows = (size_t)2 * m->c.n_heads;
+    for (int l = 0; l < n_dec_layers(m->c); ++l) {
+        char* hl = host + (size_t)l * layer_rows * s.len * rowb;
+        for (int i = 0; i * m->blk_rows < s.len; ++i) {
+            int rows_in = std::min(m->blk_rows, s.len - i * m->blk_rows);
+            char* dev = (char*)layer_blocks(m, l) + (size_t)s.blocks[i] * m->blk_elems * m->esz;
+            char* hp = hl + (size_t)i * m->blk_rows * rowb;
+            hipError_t e = to_host ? hipMemcpy2DAsync(hp, s.len * rowb, dev, m->blk_rows * rowb, rows_in * rowb, layer_rows,
+                                                      hipMemcpyDeviceToHost, m->stream)
+                                   : hipMemcpy2DAsync(dev, m->blk_rows * rowb, hp, s.len * rowb, rows_in * rowb, layer_rows,
+                                                      hipMemcpyHostToDevice, m->stream);
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
 static uint64_t export_bytes_of(const exe_model* m, const Seq& s)
 {
     uint64_t rows = (uint64_t)n_dec_layers(m->c) * 2 * m->c.n_heads;
@@ -928,7 +1052,10 @@ extern "C" int exe_seq_export(exe_model_t* m, int32_t seq_id, void* host_buf, ui
     if (buf_bytes < need) return fail(EXE_ERR_ARG, "buffer of %llu bytes, %llu needed", (unsigned long long)buf_bytes, (unsigned long long)need);
     size_t rows = (size_t)n_dec_layers(m->c) * 2 * m->c.n_heads, rowb = (size_t)m->c.head_dim * m->esz;
     char* dst = (char*)host_buf;
-    if (s.len > 0) {
+    if (s.len > 0 && paged(m)) {
+        HIP_TRY(copy_blocks(m, s, dst, true));
+        dst += rows * s.len * rowb;
+    } else if (s.len > 0) {
         HIP_TRY(hipMemcpy2DAsync(dst, s.len * rowb, (const char*)m->pool.ptr + s.base * m->esz, s.cap * rowb, s.len * rowb, rows,
                                  hipMemcpyDeviceToHost, m->stream));
         dst += rows * s.len * rowb;
@@ -963,6 +1090,22 @@ extern "C" int exe_seq_import(exe_model_t* m, int32_t seq_id, const void* host_b
     if (learned && !encdec && cap > c.max_pos) cap = c.max_pos;
     s.cap = round8(cap);
     int ndl = n_dec_layers(c);
+    if (paged(m)) {
+        int need = blocks_for(m, std::max(s.len, 1));
+        if (need > (int)m->free_blocks.size())
+            return fail(EXE_ERR_OOM_KV, "K/V pool exhausted (%d blocks needed, %d of %d free)", need, (int)m->free_blocks.size(), m->n_blocks);
+        take_blocks(m, s, need);
+        hipError_t e = copy_blocks(m, s, (char*)const_cast<void*>(host_buf), false);
+        if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+        if (e != hipSuccess) {
+            for (auto it = s.blocks.rbegin(); it != s.blocks.rend(); ++it) m->free_blocks.push_back(*it);
+            return fail(EXE_ERR_HIP, "K/V import copy: %s", hipGetErrorString(e));
+        }
+        s.live = true;
+        m->seqs[seq_id] = s;
+        m->live++;
+        return EXE_OK;
+    }
     s.elems = (int64_t)ndl * 2 * m->inner * s.cap;
     s.base = m->pool.alloc(s.elems);
     if (s.base >= 0 && encdec) {
@@ -1007,6 +1150,19 @@ extern "C" int exe_seq_reserve(exe_model_t* m, int32_t seq_id, int32_t reserve_l
     if (reserve_length < std::max(s.len, 1)) return fail(EXE_ERR_BAD_LENGTH, "reserve length %d below the current length %d", reserve_length, s.len);
     if (learned && c.arch != EXE_ARCH_ENC_DEC && reserve_length > c.max_pos)
         return fail(EXE_ERR_BAD_LENGTH, "reserve length %d exceeds max_pos %d", reserve_length, c.max_pos);
+    if (paged(m)) {
+        // blocks ahead of need, or surplus blocks back to the pool
+        int want = blocks_for(m, reserve_length), have = (int)s.blocks.size();
+        if (want - have > (int)m->free_blocks.size())
+            return fail(EXE_ERR_OOM_KV, "K/V pool exhausted (%d blocks needed, %d of %d free)", want - have, (int)m->free_blocks.size(), m->n_blocks);
+        if (want > have) take_blocks(m, s, want - have);
+        while ((int)s.blocks.size() > want) {
+            m->free_blocks.push_back(s.blocks.back());
+            s.blocks.pop_back();
+        }
+        s.cap = (int)s.blocks.size() * m->blk_rows;
+        return EXE_OK;
+    }
     int cap = round8(reserve_length);
     if (cap == s.cap) return EXE_OK;
     int64_t elems = (int64_t)n_dec_layers(c) * 2 * m->inner * cap;
@@ -1032,6 +1188,7 @@ extern "C" int exe_kv_compact(exe_model_t* m, uint64_t* moved_bytes)
 {
     if (!m) return fail(EXE_ERR_ARG, "null model");
     if (moved_bytes) *moved_bytes = 0;
+    if (paged(m)) return EXE_OK;           // blocks are interchangeable: nothing to compact
     struct Ext { int64_t base, elems; int seq; bool cross; };
     std::vector<Ext> ex;
     for (int i = 0; i < m->c.max_seqs; ++i) {
@@ -1085,6 +1242,14 @@ extern "C" int exe_kv_stats(exe_model_t* m, uint64_t* pool_bytes, uint64_t* used
                             int32_t* live_seqs)
 {
     if (!m) return fail(EXE_ERR_ARG, "null model");
+    if (paged(m)) {
+        uint64_t blk = (uint64_t)n_dec_layers(m->c) * m->blk_elems * m->esz;      // one block id across all layers
+        if (pool_bytes) *pool_bytes = blk * m->n_blocks;
+        if (used_bytes) *used_bytes = blk * (m->n_blocks - m->free_blocks.size());
+        if (largest_free_bytes) *largest_free_bytes = blk * m->free_blocks.size();
+        if (live_seqs) *live_seqs = m->live;
+        return EXE_OK;
+    }
     if (pool_bytes) *pool_bytes = (uint64_t)m->pool.elems * m->esz;
     if (used_bytes) *used_bytes = (uint64_t)m->pool.used * m->esz;
     if (largest_free_bytes) *largest_free_bytes = (uint64_t)m->pool.largest() * m->esz;

@@ -19,12 +19,12 @@ def kv_bytes_per_token(shape):
 
 
 def make_pair(shape, seed, real="double", pool_tokens=8192, max_seqs=64, max_batch_tokens=4096, max_batch_seqs=64,
-              gen_device="cpu"):
+              gen_device="cpu", kv_block_size=0):
     """Returns (hip model, oracle, device weights).  Weights are drawn once and shared by value."""
     w = wl.make_weights(shape, seed, device=gen_device)
     wd = [t.to(DEV) for t in w]
     cfg = exe.config_from_shape(shape, kv_pool_bytes=pool_tokens * kv_bytes_per_token(shape), max_seqs=max_seqs,
-                                max_batch_tokens=max_batch_tokens, max_batch_seqs=max_batch_seqs)
+                                max_batch_tokens=max_batch_tokens, max_batch_seqs=max_batch_seqs, kv_block_size=kv_block_size)
     m = exe.Model(cfg, wd)
     o = oracle.Oracle(shape, w, real, max_seqs=max_seqs)
     return m, o, wd

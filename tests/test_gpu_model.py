@@ -15,11 +15,12 @@ F32_TOL = 1e-4
 
 
 def run_decoder_only(shape, seed, in_lens, n_steps, tol, real="double", check_tokens=False, release_at=None,
-                     gen_device="cpu"):
+                     gen_device="cpu", kv_block_size=0):
     """Encode a batch, then n_steps decode steps feeding the ORACLE's greedy tokens to both sides, so that a
     near-tie cannot make the two sides diverge; compares logits at every step."""
     n = len(in_lens)
-    m, o, _ = make_pair(shape, seed, real, gen_device=gen_device, max_batch_tokens=max(4096, int(sum(in_lens))))
+    m, o, _ = make_pair(shape, seed, real, gen_device=gen_device, max_batch_tokens=max(4096, int(sum(in_lens))),
+                        kv_block_size=kv_block_size)
     rng = np.random.default_rng(seed)
     toks = wl.random_tokens(rng, int(sum(in_lens)), shape.vocab)
     ids = np.arange(n) + 3
