@@ -140,14 +140,18 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
 
     // with a fused append the cached rows are 0 .. nk-2; the new row is folded in after the loop
     const int nc = (!PACKED && knew) ? nk - 1 : nk;
+    // PAGED: the block of a step is looked up one step ahead, so that the step's loads do not wait for the table
+    int blk = (PAGED && wave * RPW * U < nc) ? tbl[(wave * RPW * U) >> block_shift] : 0;
     for (int j0 = wave * RPW * U; j0 < nc; j0 += NWV * RPW * U) {
         uint4 kc[U], vc[U];
         float s[U];
         int jb = 0;                           // PAGED: first row of the block that holds rows j0 .. j0 + RPW*U - 1
         if (PAGED) {
-            kp = block_k(tbl[j0 >> block_shift]);
+            kp = block_k(blk);
             vp = kp + (int64_t)H * block_rows * DH;
             jb = j0 & ~(block_rows - 1);
+            int jn = j0 + NWV * RPW * U;
+            if (jn < nc) blk = tbl[jn >> block_shift];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
