@@ -18,6 +18,7 @@
 namespace exe {
 
 constexpr float LOG2E = 1.44269504088896340736f;
+constexpr int ATTN_BIAS_LDS = 1024;       // entries of a head's bias table that the row kernel keeps in LDS
 constexpr int ATTN_SHORT_LEN = 320;      // decode attention: mean rows per sequence up to which 4 waves serve a row
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -133,6 +134,18 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
         for (int e = 0; e < EPL; ++e) qf[e] = t[e] * scale * LOG2E;
     }
     const float* bias = bias_by_dist ? bias_by_dist + (int64_t)h * (2 * radius + 1) + radius : nullptr;
+    // The head's bias table goes to LDS first (scaled for exp2): a look-up in global memory shares the wave's
+    // in-order load counter with the K/V stream and cost 12 % of the kernel's bandwidth.
+    __shared__ float s_bias[ATTN_BIAS_LDS];
+    const bool bias_lds = bias && 2 * radius + 1 <= ATTN_BIAS_LDS;
+    if (bias_lds) {
+        for (int i = threadIdx.x; i < 2 * radius + 1; i += NWV * 64) s_bias[i] = bias[i - radius] * LOG2E;
+        __syncthreads();
+    }
+    auto bias_at = [&](int rel) {
+        rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
+        return bias_lds ? s_bias[rel + radius] : bias[rel] * LOG2E;
+    };
 
     float m_run = -INFINITY, l_run = 0.f, acc[EPL];
 #pragma unroll
@@ -171,11 +184,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
 #pragma unroll
             for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
             int j = j0 + u * RPW + rg;
-            if (bias) {
-                int rel = j - qpos;
-                rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
-                d += bias[rel] * LOG2E;
-            }
+            if (bias) d += bias_at(j - qpos);
             s[u] = j < nc ? d : -INFINITY;
             mx = fmaxf(mx, s[u]);
         }
@@ -207,11 +216,7 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
         for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kf[e], d);
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, WAVE);
-        if (bias) {
-            int rel = nk - 1 - qpos;
-            rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
-            d += bias[rel] * LOG2E;
-        }
+        if (bias) d += bias_at(nk - 1 - qpos);
         float mx = fmaxf(m_run, d);
         float alpha = fast_exp2(m_run - mx), p = fast_exp2(d - mx);
         l_run = l_run * alpha + p;
