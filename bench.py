@@ -288,6 +288,14 @@ def main():
         out["roofline_decode_sampling"] = f"decode classes timed on every {every}th iteration"
         enc_flops = sum(a["flops"] for a in acc["encode"].values())
         out["encode_frac_of_mfma_peak"] = round(enc_flops / (t_enc / K) / PEAK_MFMA_BF16, 4)
+        # what this machine sustains with nothing but loads / nothing but MFMAs, measured now (the fractions above stay
+        # against the nominal peaks)
+        torch.cuda.synchronize()
+        pk = exe.exe_probe_peaks()
+        ach = {"hbm": pk["hbm_read_bytes_per_s"] / 1e9, "mfma": pk["mfma_bf16_flops_per_s"] / 1e12}
+        out["achievable"] = {"hbm_read_GBps": round(ach["hbm"], 1), "mfma_bf16_TFLOPs": round(ach["mfma"], 1),
+                             "how": "streaming read of 4 GiB; back-to-back 16x16x32 bf16 MFMAs on every CU"}
+        out["roofline"]["frac_of_achievable"] = round(dom["achieved"] / ach[dom["bound"]], 4)
     if args.rra and shape.has_embed:
         rng = np.random.default_rng(wl.BASE_SEED + 17)
         big = {"opt13b": wl.workload_opt13b, "t5_11b": wl.workload_t5}[args.workload](3 * job.n, seed=wl.BASE_SEED + 17)

@@ -306,6 +306,12 @@ int exe_op_decode_attention_paged(void* hip_stream, int32_t dtype, int32_t B, co
                                   int32_t block_size, const int32_t* len, const int32_t* qpos, int32_t H, int32_t dh,
                                   float scale, const float* bias_by_dist, int32_t bias_radius, int32_t new_kv_offset,
                                   void* out);
+/* Measured ceilings of this machine, to set beside the nominal peaks when a kernel is judged against its roofline
+ * (no part of the method; the paper's evaluation, Section 7, likewise reads its numbers against what its GPUs
+ * sustain): *hbm_read_bytes_per_s = rate of a plain streaming read of read_bytes bytes (0 = 4 GiB; allocated and
+ * freed by the call), *mfma_bf16_flops_per_s = rate of back-to-back bf16 16x16x32 MFMAs on all compute units at the
+ * clock that load sustains.  Either pointer may be NULL.  Synchronises the stream; host pointers. */
+int exe_probe_peaks(void* hip_stream, uint64_t read_bytes, double* hbm_read_bytes_per_s, double* mfma_bf16_flops_per_s);
 /* argmax over each row of float logits [rows, n] -> int32 out [rows]; lowest index on ties */
 int exe_op_argmax(void* hip_stream, const float* logits, int32_t rows, int32_t n, int32_t* out);
 /* T5 bucket of rel = key - query as this library computes it (host function, exact integer arithmetic) */

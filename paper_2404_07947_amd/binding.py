@@ -14,7 +14,7 @@ DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
     "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_seq_reserve", "exe_kv_compact", "exe_profile", "exe_run_rra", "exe_kernel_timing",
     "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_norm", "exe_op_prefill_attention",
-    "exe_op_decode_attention", "exe_op_decode_attention_paged", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
+    "exe_op_decode_attention", "exe_op_decode_attention_paged", "exe_probe_peaks", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
     # exe_sched.h (host only)
     "exe_sim_completion", "exe_sim_step_ms", "exe_sim_rra", "exe_sim_waa", "exe_sched_search", "exe_sched_rra",
 ]
@@ -353,6 +353,15 @@ def exe_op_decode_attention_paged(dtype, B, q, q_stride, kv_blocks, block_table,
     _check(lib().exe_op_decode_attention_paged(_stream_ptr(stream), dtype, B, _dev(q), q_stride, _dev(kv_blocks),
                                                _dev(block_table), max_blocks, block_size, _dev(length), _dev(qpos), H, dh,
                                                scale, _dev(bias_by_dist), bias_radius, new_kv_offset, _dev(out)))
+
+
+def exe_probe_peaks(read_bytes: int = 0, stream=None) -> dict:
+    """Measured streaming-read and bf16 MFMA rates of the current device."""
+    L = lib()
+    L.exe_probe_peaks.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    r, f = C.c_double(), C.c_double()
+    _check(L.exe_probe_peaks(_stream_ptr(stream), read_bytes, C.byref(r), C.byref(f)))
+    return {"hbm_read_bytes_per_s": r.value, "mfma_bf16_flops_per_s": f.value}
 
 
 def exe_op_argmax(logits, rows, n, out, stream=None):

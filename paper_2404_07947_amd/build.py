@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libexe.so")
-SOURCES = ["kernels_elementwise.hip", "kernels_gemm.hip", "kernels_attn.hip", "runtime.hip", "sched.cpp"]
+SOURCES = ["kernels_elementwise.hip", "kernels_gemm.hip", "kernels_attn.hip", "runtime.hip", "probe.hip", "sched.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

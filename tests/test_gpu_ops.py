@@ -148,6 +148,12 @@ def test_argmax_lowest_index_on_ties():
     assert want[1:] == [123, 0, n - 1, 0]
 
 
+def test_probe_peaks_are_plausible():
+    pk = exe.exe_probe_peaks()
+    assert 2e12 < pk["hbm_read_bytes_per_s"] < 8.5e12            # below the nominal 8 TB/s, well above a PCIe-class rate
+    assert 0.5e15 < pk["mfma_bf16_flops_per_s"] < 2.6e15         # below the nominal 2.5 PFLOP/s
+
+
 # ------------------------------------------------------------------ attention
 def oracle_attention(q, K, V, scale, bias=None):
     return prim().attention_row(q, K, V, scale, bias)[0]
