@@ -81,6 +81,22 @@ __device__ __forceinline__ float block_sum(float v, float* red)
     return t;
 }
 
+// four consecutive elements (k is a multiple of 4, rows start at multiples of 4 elements) as one access
+__device__ __forceinline__ f32x4 load4(const float* p) { return *(const f32x4*)p; }
+__device__ __forceinline__ f32x4 load4(const bf16_t* p)
+{
+    uint2 u = *(const uint2*)p;
+    return f32x4{bf16lo(u.x), bf16hi(u.x), bf16lo(u.y), bf16hi(u.y)};
+}
+__device__ __forceinline__ void store4(float* p, f32x4 v) { *(f32x4*)p = v; }
+__device__ __forceinline__ void store4(bf16_t* p, f32x4 v)
+{
+    bf16x4 w;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = (bf16_t)v[j];
+    *(bf16x4*)p = w;
+}
+
 template <typename T, bool RMS>
 __global__ void norm_kernel(const float* __restrict__ x, const int32_t* __restrict__ row_index, int d,
                             const T* __restrict__ gain, const T* __restrict__ shift, float eps, float out_scale,
@@ -115,12 +131,10 @@ __global__ void norm_kernel(const float* __restrict__ x, const int32_t* __restri
     T* o = out + (int64_t)r * d;
     for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
         f32x4 v = *(const f32x4*)(row + k);
+        f32x4 g = load4(gain + k), b = RMS ? f32x4{0.f, 0.f, 0.f, 0.f} : load4(shift + k), y;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float y = (v[j] - mean) * rstd * to_f32(gain[k + j]);
-            if (!RMS) y += to_f32(shift[k + j]);
-            o[k + j] = from_f32<T>(y * out_scale);
-        }
+        for (int j = 0; j < 4; ++j) y[j] = ((v[j] - mean) * rstd * g[j] + b[j]) * out_scale;
+        store4(o + k, y);
     }
 }
 
