@@ -142,3 +142,52 @@ def test_relocation_errors_change_nothing():
     m.seq_reserve(0, 48)                                                                 # fits beside the old extent
     assert m.kv_stats()["used_bytes"] == 48 * kv_bytes_per_token(shape)
     m.close()
+
+
+@pytest.mark.parametrize("first_reserve,moves", [(32, True), (8, False)])
+def test_compaction_moves_an_extent_over_itself_in_pieces_or_leaves_it(first_reserve, moves):
+    # a long extent behind a short released one: the move overlaps its own source and goes in 1024 / 32 = 32 pieces;
+    # behind an extent of 8 positions it would take 128 pieces, more than the limit of 64, and the extent stays
+    shape = wl.tiny_shape().replace(name="tiny_long", max_pos=1024)
+    m, o, _ = make_pair(shape, wl.BASE_SEED + 9, "float", pool_tokens=2048, max_seqs=8, max_batch_tokens=256, max_batch_seqs=8)
+    rng = np.random.default_rng(33)
+    L = 40
+    toks = wl.random_tokens(rng, 5 + L, shape.vocab)
+    steps = 6
+    t, _ = o.encode(0, toks[5:])
+    want = [t]
+    for _ in range(steps):
+        t, _ = o.decode(0, t)
+        want.append(t)
+    m.encode([0], [5], toks[:5], reserve_lengths=[first_reserve])
+    cur = m.encode([1], [L], toks[5:], reserve_lengths=[1024])
+    got = [int(cur[0])]
+    for s in range(1, 4):
+        cur = m.decode_step([1], cur, [L + s])
+        got.append(int(cur[0]))
+    m.seq_release([0])
+    buf0, st0 = m.seq_export(1)
+    moved = m.kv_compact()
+    st = m.kv_stats()
+    if moves:
+        assert moved == 1024 * kv_bytes_per_token(shape)
+        assert st["largest_free_bytes"] == st["pool_bytes"] - st["used_bytes"]
+    else:
+        assert moved == 0 and st["largest_free_bytes"] < st["pool_bytes"] - st["used_bytes"]
+    buf1, st1 = m.seq_export(1)
+    assert st0 == st1 and np.array_equal(buf0, buf1)
+    for s in range(4, steps + 1):
+        cur = m.decode_step([1], cur, [L + s])
+        got.append(int(cur[0]))
+    assert got == want
+    # the free list is consistent: a sequence that needs the whole remainder is admitted exactly when it is one piece
+    free_tokens = (st["pool_bytes"] - st["used_bytes"]) // kv_bytes_per_token(shape)
+    t2 = wl.random_tokens(rng, 3, shape.vocab)
+    if moves:
+        m.encode([2], [3], t2, reserve_lengths=[int(free_tokens)])
+        assert m.kv_stats()["used_bytes"] == st["pool_bytes"]
+    else:
+        with pytest.raises(exe.ExeError) as e:
+            m.encode([2], [3], t2, reserve_lengths=[int(free_tokens)])
+        assert e.value.code == -3
+    m.close()
