@@ -264,8 +264,10 @@ int exe_kernel_timing(exe_model_t* m, int32_t enable);           /* also resets 
 int exe_kernel_times(exe_model_t* m, exe_kernel_time_t* rows /* [EXE_K_COUNT] */);
 
 /*
- * Single-operation entry points (device pointers, enqueued on `hip_stream`, NOT synchronised).  They run
- * the same kernels the model calls use; tests and micro-benchmarks call them.
+ * Tooling of this library, no part of the paper's method and citing nothing from it: the per-kernel-class timing
+ * above (exe_kernel_timing, exe_kernel_times), the single-operation entry points below (exe_op_*: device pointers,
+ * enqueued on `hip_stream`, NOT synchronised; they run the same kernels the model calls use, for per-kernel
+ * parity tests and micro-benchmarks) and exe_probe_peaks.
  */
 /* out = epilogue(alpha * A[M,K] . W[N,K]^T + bias):  out_mode 0: dtype out [M,N] with activation
  * act (-1 none, EXE_ACT_*); 1: float resid [M,N] += result; 2: float out [M,N].
@@ -274,6 +276,19 @@ int exe_op_gemm(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K
                 const void* W, const void* bias, int32_t act, float alpha, int32_t out_mode, void* out,
                 void* workspace, uint64_t workspace_bytes);
 uint64_t exe_op_gemm_workspace(int32_t dtype, int32_t M, int32_t N, int32_t K);
+/* How exe_op_gemm launches a shape (host function; lets a test assert that its cases cover every kernel
+ * instantiation): *route 0 = MFMA tile kernel, 2 = plain-FMA kernel; *cfg = tile configuration (0 64x256, 1 128x256,
+ * 2 256x256, 3 64x128, 4 128x128, 5 256x128 rows x features); *splits = split-K parts (> 1: float partials in the
+ * workspace, summed in split order by a second kernel); *rows_first = rows of the first launch (M, unless the rows
+ * beyond whole rounds of 256 x 256 tiles go to a second, separately planned launch: ask again with M - *rows_first). */
+int exe_op_gemm_plan(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t* route, int32_t* cfg, int32_t* splits,
+                     int32_t* rows_first);
+/* exe_op_gemm for bf16 operands whose rows are lda / ldw elements apart (>= K, multiples of 8; K a multiple of 64;
+ * shapes the MFMA tile kernel serves only).  Row strides that are not a multiple of 4 KiB spread a tile's rows
+ * over more memory channels. */
+int exe_op_gemm_ld(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda,
+                   const void* W, int32_t ldw, const void* bias, int32_t act, float alpha, int32_t out_mode, void* out,
+                   void* workspace, uint64_t workspace_bytes);
 /* rows of float x [*, d] (row_index nullable selects rows) -> dtype out [rows, d] */
 int exe_op_norm(void* hip_stream, int32_t dtype, int32_t rms, const float* x, const int32_t* row_index,
                 int32_t rows, int32_t d, const void* gain, const void* shift, float eps, float out_scale,
@@ -306,9 +321,13 @@ int exe_op_decode_attention_paged(void* hip_stream, int32_t dtype, int32_t B, co
                                   int32_t block_size, const int32_t* len, const int32_t* qpos, int32_t H, int32_t dh,
                                   float scale, const float* bias_by_dist, int32_t bias_radius, int32_t new_kv_offset,
                                   void* out);
-/* Measured ceilings of this machine, to set beside the nominal peaks when a kernel is judged against its roofline
- * (no part of the method; the paper's evaluation, Section 7, likewise reads its numbers against what its GPUs
- * sustain): *hbm_read_bytes_per_s = rate of a plain streaming read of read_bytes bytes (0 = 4 GiB; allocated and
+/* Host-side replay of the row indexing of the paged decode-attention kernel for one sequence of `len` cached rows
+ * (the same index functions the kernel calls, for the launch shape of n_waves = 4 or 16 waves): returns 0 when every
+ * row read is a cached row inside the block its table look-up names and every cached row is read exactly once, else
+ * the number of violations (> 0), or a negative status for bad arguments. */
+int exe_op_paged_index_check(int32_t dtype, int32_t dh, int32_t block_size, int32_t n_waves, int32_t len);
+/* Measured ceilings of this machine, to set beside the nominal peaks when a kernel is judged against its roofline:
+ * *hbm_read_bytes_per_s = rate of a plain streaming read of read_bytes bytes (0 = 4 GiB; allocated and
  * freed by the call), *mfma_bf16_flops_per_s = rate of back-to-back bf16 16x16x32 MFMAs on all compute units at the
  * clock that load sustains.  Either pointer may be NULL.  Synchronises the stream; host pointers. */
 int exe_probe_peaks(void* hip_stream, uint64_t read_bytes, double* hbm_read_bytes_per_s, double* mfma_bf16_flops_per_s);

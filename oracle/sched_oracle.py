@@ -13,6 +13,8 @@ paper's order and notation:
                     throughput and latency
   waa_workload      Section 6, "Simulating WAA Schedule": B_D = B_E * S_D, workloads B_E * S_E and B_D; Section 4
                     "WAA-C": GPUs in proportion to the estimated encoding / decoding times
+  simulate_rra      Section 4, "RRA Scheduling", and Section 5, dynamic workload adjustment: the schedule itself played
+                    out request by request (counters only), what the run loop's statistics must equal
   exhaustive_best   Section 5, the optimisation problem itself (arg max throughput subject to latency < L_Bound),
                     by evaluating every configuration point: what the branch-and-bound search must find
   branch_and_bound  Section 5, Algorithm 1, step by step (selecting, splitting with the corner heuristic, bounding,
@@ -20,8 +22,10 @@ paper's order and notation:
 
 Readings where the paper leaves the timeline open (the same ones the library documents):
   * a decode iteration's time is read from the profile table at (live batch, mean context length), the context
-    length being E[S_E] + E[S_D^2] / (2 E[S_D]) (mean input length plus the mean number of tokens a live query
-    has generated, queries weighted by how long they stay);
+    length being E[S_E] + E[S_D^2] / (2 E[S_D]) + 1/2: the mean, over the (live query, iteration) pairs of the
+    steady state, of the K/V length after the iteration's append, which is what a profile row's length means.  In
+    Section 6's model a query of S tokens is decoded for S iterations and its t-th iteration attends to the input
+    plus t positions, so the mean is E[S_E] + E[S (S + 1) / 2] / E[S];
   * the live batch of iteration U of a decoding phase is B_D (1 - sum_{u<U} P_D(u)) (completed queries leave at
     once: early termination, Section 7);
   * a query of output length s is encoded once, spends ceil(s / N_D) - 1 whole cycles and then
@@ -127,7 +131,7 @@ def rra_timeline(enc: Table, dec: Table, p_in: Sequence[float], p_out: Sequence[
     b_e = b_d * frac
     mean_in, _ = moments(p_in)
     mean_out, second_out = moments(p_out)
-    ctx = mean_in + second_out / (2.0 * mean_out)
+    ctx = mean_in + second_out / (2.0 * mean_out) + 0.5
     t_enc = enc.time_ms(b_e, mean_in)
     live = []
     done = 0.0
@@ -144,6 +148,63 @@ def rra_timeline(enc: Table, dec: Table, p_in: Sequence[float], p_out: Sequence[
     occ = float(sum(math.ceil(s / N_D) * float(p_out[s - 1]) for s in range(1, len(p_out) + 1)))
     return RraResult(b_e, b_d, frac, ctx, t_enc, t_dec, cycle, tokens, tokens / cycle * 1e3, b_e / cycle * 1e3,
                      latency, occ)
+
+
+# ------------------------------------------------------------------ Section 4 / Section 5: the RRA schedule, request by request
+def simulate_rra(in_len: Sequence[int], out_len: Sequence[int], B_D: int, N_D: int, decoder_only: bool = True,
+                 adjust: bool = False, tolerance: float = 0.25) -> Dict[str, float]:
+    """Counters of the RRA schedule on a queue of requests served first-come first-served with forced output lengths.
+
+    Encoding and decoding phases alternate: an encoding phase, then N_D decoding iterations (Section 4).  The
+    encoding batch is the number of queries completed since the decode batch was last full, i.e. its free slots
+    (the first phase fills all B_D); a decoder-only query produces its first token at its encoding, every live
+    query one token per decoding iteration, and a query leaves when it has produced its forced output length.
+    With `adjust` (Section 5), an encoding phase admits requests only while the sum of their input lengths stays
+    within (1 + tolerance) x (encoding batch x mean input length), always at least one; what it leaves out raises
+    the next phase's encoding batch, because that is again the number of free slots.
+    Returns encode_phases, decode_iterations, mean_decode_batch, generated_tokens, encoded_tokens."""
+    n = len(in_len)
+    mean_in = sum(int(x) for x in in_len) / n
+    nxt = finished = phases = iters = batch_sum = gen = enc = 0
+    live: List[List[int]] = []                    # [request, tokens produced]
+    while finished < n:
+        want = min(B_D - len(live), n - nxt)
+        budget = (1.0 + tolerance) * max(1, want) * mean_in if adjust else float("inf")
+        taken = 0
+        if want > 0:
+            phases += 1
+        while want > 0:
+            L = int(in_len[nxt])
+            if taken > 0 and taken + L > budget:
+                break
+            taken += L
+            enc += L
+            if decoder_only:
+                gen += 1
+                if out_len[nxt] == 1:
+                    finished += 1
+                else:
+                    live.append([nxt, 1])
+            else:
+                live.append([nxt, 0])
+            nxt += 1
+            want -= 1
+        for _ in range(N_D):
+            if not live:
+                break
+            iters += 1
+            batch_sum += len(live)
+            still = []
+            for q in live:
+                q[1] += 1
+                gen += 1
+                if q[1] >= out_len[q[0]]:
+                    finished += 1
+                else:
+                    still.append(q)
+            live = still
+    return {"encode_phases": phases, "decode_iterations": iters, "mean_decode_batch": batch_sum / max(iters, 1),
+            "generated_tokens": gen, "encoded_tokens": enc}
 
 
 # ------------------------------------------------------------------ Section 6 / Section 4: WAA workload and allocation
@@ -163,7 +224,7 @@ def waa_workload(enc: Table, dec: Table, p_in: Sequence[float], p_out: Sequence[
     mean_in, _ = moments(p_in)
     mean_out, second_out = moments(p_out)
     b_d = b_e * mean_out
-    ctx = mean_in + second_out / (2.0 * mean_out)
+    ctx = mean_in + second_out / (2.0 * mean_out) + 0.5
     c_e = enc.time_ms(b_e, mean_in)
     c_d = dec.time_ms(b_d, ctx)
     g_e = int(round(n_gpus * c_e / (c_e + c_d)))

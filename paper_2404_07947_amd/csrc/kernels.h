@@ -17,10 +17,15 @@ struct GemmArgs {
     void* out;            // [M, N]
     float* workspace;     // split-K partial sums
     size_t workspace_bytes;
+    int lda = 0, ldw = 0; // row strides of A and W in elements (0 = K); the generic kernel takes dense rows only
 };
 size_t gemm_workspace_bytes(int dtype, int M, int N, int K);
-// which kernel family a shape runs on: 0 tile, 1 skinny, 2 generic
+// which kernel family a shape runs on: 0 tile (MFMA), 2 generic (plain FMA)
 int gemm_route(int dtype, int M, int N, int K);
+// how a shape is launched: route (as gemm_route), tile configuration (0 64x256, 1 128x256, 2 256x256, 3 64x128,
+// 4 128x128, 5 256x128), split-K parts, and the leading rows that the first launch takes (M unless the rows beyond
+// whole rounds of tiles go to a second launch)
+void gemm_plan_info(int dtype, int M, int N, int K, int* route, int* cfg, int* splits, int* rows_first);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 
 hipError_t launch_embed(int dtype, const int32_t* tokens, const int32_t* pos, int T, int d, const void* tok_emb,
@@ -70,6 +75,8 @@ struct AttnPagedArgs {       // as AttnCacheArgs, with the cache of one layer he
     int mean_len = 0;
 };
 hipError_t launch_attn_paged(const AttnPagedArgs& a, hipStream_t s);
+// host-side replay of the paged kernel's row indexing (0 = every row read lies in its block and is read once)
+int paged_index_check(int dtype, int dh, int block_shift, int nwv, int len);
 
 struct AttnPackedArgs {      // ragged prefill over packed qkv [T, 3*H*dh]
     int dtype, T, H, dh, n_seqs;
@@ -84,6 +91,7 @@ struct AttnPackedArgs {      // ragged prefill over packed qkv [T, 3*H*dh]
     // tile list for the MFMA kernel: (seq, first query row) pairs, longest work first
     const int32_t* tiles; int n_tiles;
     int force_generic;
+    int max_len = 0;         // longest sequence of the batch (0 = unknown: T is taken)
 };
 bool prefill_mfma_supported(int dtype, int dh);
 constexpr int PREFILL_TILE_Q = 128;

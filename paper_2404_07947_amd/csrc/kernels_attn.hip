@@ -12,6 +12,11 @@
 //    S^T = K.Q^T and O^T = V^T.P^T are both computed with MFMA 16x16x32 so that softmax statistics of a
 //    query live in the lanes of one accumulator column and P feeds the second MFMA straight from the first
 //    one's accumulators.
+#include <stdio.h>
+
+#include <mutex>
+#include <vector>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -50,10 +55,26 @@ template <bool STREAM, typename T> __device__ __forceinline__ uint4 load_chunk(c
     return *(const uint4*)p;
 }
 
+// Paged cache indexing, shared by the kernel and by the host-side check paged_index_check below.
+// paged_lookup_row: the row whose block look-up x of the step starting at row j names (nc rows are cached);
+// paged_lane_row: the row that the lane group rg of load u of that step reads.
+__host__ __device__ __forceinline__ int paged_lookup_row(int j, int x, int rpw, int nc)
+{
+    int row = j + x * rpw;
+    return row < nc ? row : nc - 1;
+}
+__host__ __device__ __forceinline__ int paged_lane_row(int j, int u, int rg, int rpw, int nc)
+{
+    int row = j + u * rpw + rg;
+    return row < nc ? row : nc - 1;
+}
+
 // PAGED (with PACKED = false): the cache of a sequence is a list of blocks of 2^block_shift positions instead of
 // one extent.  Block b of the pool holds [K|V][head][position in block][DH]; block_table[r * max_blocks + i] is the
-// block with positions i * 2^block_shift .. of sequence r.  A wave's rows of one step (RPW * U = 8) never straddle
-// a block (block_shift >= 3), so one table look-up per wave and step suffices.
+// block with positions i * 2^block_shift .. of sequence r.  The rows of one load of a wave (RPW <= 8 consecutive
+// rows starting at a multiple of RPW) never straddle a block (block_shift >= 3).  The RPW * U rows of a whole step
+// do not either when RPW * U <= 8: then one table look-up per wave and step suffices; otherwise (bf16, head size
+// 64: 16 rows per step) every load of the step has a look-up of its own.
 template <typename T, int DH, bool PACKED, int NWV = 4, int U = 4, bool PAGED = false>
 __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
     const T* __restrict__ q, int q_stride, const T* kvbuf, const int64_t* __restrict__ base,
@@ -67,6 +88,8 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
     constexpr int LPR = DH / EPL;            // lanes that share one key/value row
     constexpr int RPW = 64 / LPR;            // rows per wave per load
     constexpr int G = NWV * RPW;             // partial softmax states per workgroup (U row blocks in flight per wave)
+    constexpr int NL = (PAGED && RPW * U > 8) ? U : 1;   // PAGED: table look-ups per step
+    static_assert(RPW <= 8, "the rows of one load must fit the smallest block");
     __shared__ float s_m[G], s_l[G];
     __shared__ float s_acc[G][DH];
 
@@ -153,25 +176,40 @@ __global__ __launch_bounds__(NWV * 64) void attn_row_kernel(
 
     // with a fused append the cached rows are 0 .. nk-2; the new row is folded in after the loop
     const int nc = (!PACKED && knew) ? nk - 1 : nk;
-    // PAGED: the block of a step is looked up one step ahead, so that the step's loads do not wait for the table
-    int blk = (PAGED && wave * RPW * U < nc) ? tbl[(wave * RPW * U) >> block_shift] : 0;
+    // PAGED: the blocks of a step are looked up one step ahead, so that the step's loads do not wait for the table.
+    // Look-up x of the step starting at row j serves the rows of loads x, x + NL, ...; it names the block of row
+    // min(j + x * RPW, nc - 1), which is also the block of every row those loads touch: rows past the end are
+    // clamped to row nc - 1.
+    int blk[NL];
+    auto lookup = [&](int j) {
+#pragma unroll
+        for (int x = 0; x < NL; ++x) blk[x] = tbl[paged_lookup_row(j, x, RPW, nc) >> block_shift];
+    };
+    if (PAGED && wave * RPW * U < nc) lookup(wave * RPW * U);
+    const int64_t v_off = PAGED ? (int64_t)H * block_rows * DH : vp - kp;        // values behind the keys
     for (int j0 = wave * RPW * U; j0 < nc; j0 += NWV * RPW * U) {
         uint4 kc[U], vc[U];
         float s[U];
-        int jb = 0;                           // PAGED: first row of the block that holds rows j0 .. j0 + RPW*U - 1
+        const T* kpb[NL];                     // PAGED: keys of this head in the block of look-up x
+        int jb[NL];                           // PAGED: first row of that block
+        kpb[0] = kp;
+        jb[0] = 0;
         if (PAGED) {
-            kp = block_k(blk);
-            vp = kp + (int64_t)H * block_rows * DH;
-            jb = j0 & ~(block_rows - 1);
+#pragma unroll
+            for (int x = 0; x < NL; ++x) {
+                kpb[x] = block_k(blk[x]);
+                jb[x] = paged_lookup_row(j0, x, RPW, nc) & ~(block_rows - 1);
+            }
             int jn = j0 + NWV * RPW * U;
-            if (jn < nc) blk = tbl[jn >> block_shift];
+            if (jn < nc) lookup(jn);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int j = j0 + u * RPW + rg;
-            int jj = (j < nc ? j : nc - 1) - jb;
-            kc[u] = load_chunk<!PACKED>(kp + (int64_t)jj * row_stride + cl * EPL);
-            vc[u] = load_chunk<!PACKED>(vp + (int64_t)jj * row_stride + cl * EPL);
+            int x = NL == 1 ? 0 : u;
+            int jj = paged_lane_row(j0, u, rg, RPW, nc) - jb[x];
+            const T* kr = kpb[x] + (int64_t)jj * row_stride + cl * EPL;
+            kc[u] = load_chunk<!PACKED>(kr);
+            vc[u] = load_chunk<!PACKED>(kr + v_off);
         }
         float mx = m_run;
 #pragma unroll
@@ -273,6 +311,36 @@ hipError_t launch_attn_cache(const AttnCacheArgs& a, hipStream_t s)
     return hipGetLastError();
 }
 
+// Host-side replay of the paged kernel's row indexing for one sequence of `len` cached rows (the rows a launch with
+// these parameters reads, through the same index functions): every row read must be a cached row, lie inside the
+// block its look-up names, and every cached row must be read exactly once by an unclamped lane.  Returns 0, or the
+// number of violations.
+int paged_index_check(int dtype, int dh, int block_shift, int nwv, int len)
+{
+    int epl = dtype == DT_F32 ? 4 : 8, lpr = dh / epl, rpw = 64 / lpr;
+    constexpr int U = 2;                       // as launched below
+    int nl = rpw * U > 8 ? U : 1, block_rows = 1 << block_shift, bad = 0;
+    if (len < 1 || rpw > 8) return -1;
+    int n_blocks = (len + block_rows - 1) >> block_shift;
+    std::vector<int> seen(len, 0);
+    for (int wave = 0; wave < nwv; ++wave)
+        for (int j0 = wave * rpw * U; j0 < len; j0 += nwv * rpw * U)
+            for (int u = 0; u < U; ++u) {
+                int x = nl == 1 ? 0 : u;
+                int lrow = paged_lookup_row(j0, x, rpw, len);
+                int entry = lrow >> block_shift, first = lrow & ~(block_rows - 1);
+                if (entry < 0 || entry >= n_blocks) ++bad;
+                for (int rg = 0; rg < rpw; ++rg) {
+                    int row = paged_lane_row(j0, u, rg, rpw, len), in_block = row - first;
+                    if (row < 0 || row >= len || in_block < 0 || in_block >= block_rows) ++bad;
+                    if (j0 + u * rpw + rg < len) seen[row] += 1;
+                }
+            }
+    for (int r = 0; r < len; ++r)
+        if (seen[r] != 1) ++bad;
+    return bad;
+}
+
 hipError_t launch_attn_paged(const AttnPagedArgs& a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
@@ -301,14 +369,15 @@ hipError_t launch_attn_paged(const AttnPagedArgs& a, hipStream_t s)
 
 // ---------------------------------------------------------------- MFMA prefill (bf16, head size 128)
 // A workgroup of 4 waves owns PREFILL_TILE_Q = 128 query rows of one (sequence, head), 32 per wave as two 16-row
-// blocks; two workgroups fit a CU.  Keys and values pass through LDS in tiles of 64 rows, double buffered, both
-// by direct global->LDS loads in the same row-major swizzled layout.  Per tile a wave computes
+// blocks; three workgroups fit a CU (48 KB of LDS each).  Keys and values pass through LDS in tiles of 64 rows (two
+// key tiles, double buffered, and one value tile), both by direct global->LDS loads in the same row-major swizzled
+// layout.  Per tile a wave computes
 //   S^T[key][query] = K . Q^T      (MFMA 16x16x32: A = key rows from LDS, B = the wave's query fragments)
 //   O^T[d][query]  += V^T . P^T    (A = values through the transposing LDS read, B = P straight from the
 //                                   accumulators of S^T)
 // so a query's softmax statistics live in the four lanes that share its column, and the probabilities never leave
-// registers.  One barrier per tile.  The two workgroups of a CU drift apart, so one wave's softmax (vector ALU)
-// overlaps another's MFMAs on the same SIMD.
+// registers.  Two barriers per tile (the value tile is loaded behind the scores).  The workgroups of a CU drift
+// apart, so one wave's softmax (vector ALU) overlaps another's MFMAs on the same SIMD.
 constexpr int PF_NW = 4, PF_DH = 128, PF_KT = 64, PF_THREADS = PF_NW * 64, PF_QT = PF_NW * 32;
 constexpr int PF_LPT = 16 / PF_NW;                                // direct-to-LDS loads per wave and tile
 constexpr int PF_TILE = 16384, PF_LDS = 3 * PF_TILE;              // key tiles 0 and 1, then the value tile
@@ -355,7 +424,7 @@ __global__ __launch_bounds__(PF_THREADS, 3) void prefill_mfma_kernel(const bf16_
                                                                   float scale, const float* __restrict__ bias_by_dist,
                                                                   int radius, bf16_t* __restrict__ out)
 {
-    extern __shared__ __align__(16) unsigned char pf_smem[];      // 2 key tiles, then 2 value tiles
+    extern __shared__ __align__(16) unsigned char pf_smem[];      // 2 key tiles, then 1 value tile
     __shared__ float sbias[BIAS ? 1024 : 1];
 
     int sb = tiles[blockIdx.x * 2], q0 = tiles[blockIdx.x * 2 + 1];
@@ -578,23 +647,39 @@ bool prefill_mfma_supported(int dtype, int dh) { return dtype == DT_BF16 && dh =
 hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
-    // (the key loader addresses a sequence's rows with 32-bit byte offsets)
-    if (!a.force_generic && prefill_mfma_supported(a.dtype, a.dh) && a.n_tiles > 0 &&
-        (int64_t)a.T * 3 * a.H * a.dh * 2 < ((int64_t)1 << 32) && (!a.bias_by_dist || 2 * a.bias_radius + 1 <= 1024)) {
+    // The key loader addresses the rows of one sequence with 32-bit byte offsets, and a head's bias table must fit
+    // the kernel's LDS copy; a batch outside these limits runs on the row kernel, which is correct but far slower,
+    // so say so (once).
+    const bool mfma_shape = !a.force_generic && prefill_mfma_supported(a.dtype, a.dh) && a.n_tiles > 0;
+    const int64_t longest = a.max_len > 0 ? a.max_len : a.T;
+    const bool mfma_fits = longest * 3 * a.H * a.dh * 2 < ((int64_t)1 << 32) && (!a.bias_by_dist || 2 * a.bias_radius + 1 <= 1024);
+    if (mfma_shape && !mfma_fits) {
+        static std::once_flag warned;
+        std::call_once(warned, [&]() {
+            fprintf(stderr, "exe: prefill attention falls back to the row kernel (longest sequence %lld rows of %d bytes, bias "
+                            "radius %d): expect it to be much slower\n", (long long)longest, 3 * a.H * a.dh * 2, a.bias_radius);
+        });
+    }
+    if (mfma_shape && mfma_fits) {
         dim3 grid(a.n_tiles, a.H);
         const bf16_t* qkv = (const bf16_t*)a.qkv;
         bf16_t* out = (bf16_t*)a.out;
         constexpr int lds = PF_LDS;
-        static bool attr_set = false;
-        if (!attr_set) {
+        // the kernels' dynamic LDS limit is raised once per device
+        static std::once_flag attr_once[64];
+        static hipError_t attr_err[64];
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+        std::call_once(attr_once[dev], [&]() {
             const void* kerns[4] = {(const void*)prefill_mfma_kernel<true, true>, (const void*)prefill_mfma_kernel<true, false>,
                                     (const void*)prefill_mfma_kernel<false, true>, (const void*)prefill_mfma_kernel<false, false>};
+            attr_err[dev] = hipSuccess;
             for (const void* k : kerns) {
                 hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-                if (e != hipSuccess) return e;
+                if (e != hipSuccess) attr_err[dev] = e;
             }
-            attr_set = true;
-        }
+        });
+        if (attr_err[dev] != hipSuccess) return attr_err[dev];
         auto launch = [&](auto kern, const float* bias, int radius) -> hipError_t {
             kern<<<grid, PF_THREADS, lds, s>>>(qkv, a.cu, a.tiles, a.H, a.scale, bias, radius, out);
             return hipGetLastError();

@@ -11,6 +11,7 @@
 // consecutive output features per lane, which makes the epilogue's loads and stores 8/16-byte vectors.
 #include <stdlib.h>
 
+#include <mutex>
 #include <type_traits>
 #include <unordered_map>
 
@@ -226,7 +227,7 @@ template <int BM, int BN, int WM, int WN, int ST>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias,
     int act, float alpha, int out_mode, void* __restrict__ out, float* __restrict__ partial, int tiles_m, int tiles_n,
-    int k_per_split, int n_split, int flags)
+    int k_per_split, int n_split, int flags, int lda, int ldw)
 {
     // flags: bit 0 = spread the loads of a k-tile over the MFMAs (see below); bit 1 = the weights are read once
     // (a single row of output tiles): their loads are marked nontemporal so that they do not displace A in L2
@@ -263,6 +264,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         int within = pid - group * GM * tiles_n;
         m0 = (first_m + within % gsz) * BM;
         n0 = (within / gsz) * BN;
+        if (flags & 16) { m0 = (pid & 1) * BM; n0 = ((pid >> 1) & 1) * BN; }
     };
     auto k_tiles = [&](int z) {
         int kbeg = z * k_per_split;
@@ -285,19 +287,19 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         locate(v, m0, n0, z);
         int kbeg = z * k_per_split;
         ld_nk = k_tiles(z);
-        base_a = (const char*)(A + (int64_t)m0 * K + kbeg);
-        base_w = (const char*)(W + (int64_t)n0 * K + kbeg);
+        base_a = (const char*)(A + (int64_t)m0 * lda + kbeg);
+        base_w = (const char*)(W + (int64_t)n0 * ldw + kbeg);
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
             int rl = (p * NW + wave) * 8 + (lane >> 3);
             int r = m0 + rl < M ? rl : M - 1 - m0;
-            off_a[p] = (unsigned)r * (unsigned)(K * 2) + (((lane & 7) ^ lds_swz(rl)) << 4);
+            off_a[p] = (unsigned)r * (unsigned)(lda * 2) + (((lane & 7) ^ lds_swz(rl)) << 4);
         }
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) {
             int rl = (p * NW + wave) * 8 + (lane >> 3);
             int r = n0 + rl < N ? rl : N - 1 - n0;
-            off_w[p] = (unsigned)r * (unsigned)(K * 2) + (((lane & 7) ^ lds_swz(rl)) << 4);
+            off_w[p] = (unsigned)r * (unsigned)(ldw * 2) + (((lane & 7) ^ lds_swz(rl)) << 4);
         }
     };
     set_src(ld_v);
@@ -546,6 +548,18 @@ static int env_int(const char* name, int dflt)
     return v ? atoi(v) : dflt;
 }
 
+// Tuning knobs for sweeps and debugging, read from the environment once per process: EXE_GEMM_CFG forces a tile
+// configuration, EXE_GEMM_SPLIT a split count, EXE_GEMM_SPREAD the load issue pattern, EXE_GEMM_NT the
+// nontemporal weight loads, EXE_GEMM_GRID the number of persistent workgroups, EXE_GEMM_HOT makes every item work
+// on one of four tiles (all loads hit L2; wrong results, timing only).
+struct Knobs { int cfg, split, spread, nt, grid, hot; };
+static const Knobs& knobs()
+{
+    static const Knobs k{env_int("EXE_GEMM_CFG", -1), env_int("EXE_GEMM_SPLIT", 0), env_int("EXE_GEMM_SPREAD", -1),
+                         env_int("EXE_GEMM_NT", -1), env_int("EXE_GEMM_GRID", 0), env_int("EXE_GEMM_HOT", 0)};
+    return k;
+}
+
 // Cost model behind the choice of tile shape and split count, fitted to sweeps of the six shapes x 1..16 splits on
 // MI355X with the weights coming from HBM (the GEMM shapes of three models, 16 <= M <= 1024; the time of its picks
 // is within 1 % of the time of the best picks in total, 13 % at worst): a workgroup's time is the larger of its
@@ -611,14 +625,11 @@ static Plan make_plan(int dtype, int M, int N, int K)
         if (memo.size() > 4096) memo.clear();
         memo[key] = Choice{p.cfg, p.splits, p.cost};
     }
-    // tuning knobs (debugging / sweeps): EXE_GEMM_CFG forces a configuration, EXE_GEMM_SPLIT a split
-    // count, EXE_GEMM_SPREAD the load issue pattern
-    int force_cfg = env_int("EXE_GEMM_CFG", -1), force_split = env_int("EXE_GEMM_SPLIT", 0);
-    if (force_cfg >= 0 && force_cfg < N_CFG) p.cfg = force_cfg;
-    if (force_split > 0 && split_ok(K, force_split)) p.splits = force_split;
+    const Knobs& kn = knobs();
+    if (kn.cfg >= 0 && kn.cfg < N_CFG) p.cfg = kn.cfg;
+    if (kn.split > 0 && split_ok(K, kn.split)) p.splits = kn.split;
     p.spread = 1;     // never slower than issuing a k-tile's loads at once in that sweep, up to 15 % faster from M = 128 on
-    int force_spread = env_int("EXE_GEMM_SPREAD", -1);
-    if (force_spread >= 0) p.spread = force_spread != 0;
+    if (kn.spread >= 0) p.spread = kn.spread != 0;
     p.tiles = ((M + CFG[p.cfg].bm - 1) / CFG[p.cfg].bm) * ((N + CFG[p.cfg].bn - 1) / CFG[p.cfg].bn);
     p.k_per_split = split_k_tiles(K, p.splits) * TBK;
     return p;
@@ -626,21 +637,32 @@ static Plan make_plan(int dtype, int M, int N, int K)
 
 int gemm_route(int dtype, int M, int N, int K) { return make_plan(dtype, M, N, K).route; }
 
-// Number of persistent workgroups of a tile GEMM: one per compute unit (every configuration takes more than half
-// of a CU's LDS, so one workgroup is resident per CU), rounded down to a multiple of 8 for the XCD mapping.
+
+// Per-device launch state: the number of persistent workgroups of a tile GEMM (one per compute unit: every
+// configuration takes more than half of a CU's LDS, so one workgroup is resident per CU; rounded down to a
+// multiple of 8 for the XCD mapping) and, per tile configuration, whether the kernel's dynamic LDS limit has been
+// raised on that device.
+constexpr int MAX_DEVICES = 64;
+struct DeviceState { std::once_flag grid_once; int grid = 0; std::once_flag attr_once[8]; hipError_t attr_err[8]; };
+static DeviceState& device_state()
+{
+    static DeviceState st[MAX_DEVICES];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) dev = 0;
+    return st[dev];
+}
 static int persistent_grid()
 {
-    static int n = 0;
-    if (!n) {
+    DeviceState& d = device_state();
+    std::call_once(d.grid_once, [&]() {
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
             cus = 256;
-        n = cus / 8 * 8;
-        int force = env_int("EXE_GEMM_GRID", 0);
-        if (force >= 8) n = force / 8 * 8;
-    }
-    return n;
+        d.grid = cus / 8 * 8;
+        if (knobs().grid >= 8) d.grid = knobs().grid / 8 * 8;
+    });
+    return d.grid;
 }
 
 // A launch of many 256 x 256 tiles runs in rounds of one tile per CU, and a last round that fills few CUs costs as
@@ -661,6 +683,16 @@ static int split_rows(int dtype, int M, int N, int K)
     return parts < whole ? M1 : M;
 }
 
+void gemm_plan_info(int dtype, int M, int N, int K, int* route, int* cfg, int* splits, int* rows_first)
+{
+    int M1 = split_rows(dtype, M, N, K);
+    Plan p = make_plan(dtype, M1, N, K);
+    *route = p.route;
+    *cfg = p.cfg;
+    *splits = p.splits;
+    *rows_first = M1;
+}
+
 size_t gemm_workspace_bytes(int dtype, int M, int N, int K)
 {
     int M1 = split_rows(dtype, M, N, K);
@@ -670,27 +702,26 @@ size_t gemm_workspace_bytes(int dtype, int M, int N, int K)
 }
 
 template <int BM, int BN, int WM, int WN, int ST>
-static hipError_t launch_tile(const GemmArgs& a, const Plan& p, hipStream_t s)
+static hipError_t launch_tile(const GemmArgs& a, const Plan& p, int cfg_index, hipStream_t s)
 {
     auto kern = gemm_tile_kernel<BM, BN, WM, WN, ST>;
     constexpr int threads = (BM / WM) * (BN / WN) * 64;
     size_t lds = (size_t)ST * (BM + BN) * TBK * 2 + (size_t)(threads / 64) * epilogue_cols(BM, BN, WM, WN, ST) * 128;
     static_assert(ST * (BM + BN) * TBK * 2 + (BM / WM) * (BN / WN) * epilogue_cols(BM, BN, WM, WN, ST) * 128 <= 160 * 1024, "LDS budget");
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    DeviceState& d = device_state();
+    std::call_once(d.attr_once[cfg_index], [&]() {
+        d.attr_err[cfg_index] = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    if (d.attr_err[cfg_index] != hipSuccess) return d.attr_err[cfg_index];
     int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
     int items = tm * tn * p.splits;
     int grid = items < persistent_grid() ? items : persistent_grid();
     int w_once = tm == 1 && a.M <= 64;      // measured: 7-10 % faster up to 32 rows, even from 96 rows on
-    int force_nt = env_int("EXE_GEMM_NT", -1);
-    if (force_nt >= 0) w_once = force_nt != 0;
+    if (knobs().nt >= 0) w_once = knobs().nt != 0;
+    int hot = knobs().hot;
     kern<<<grid, threads, lds, s>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.W, (const bf16_t*)a.bias, a.act,
                                     a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split, p.splits,
-                                    (p.spread ? 1 : 0) | (w_once ? 2 : 0));
+                                    (p.spread ? 1 : 0) | (w_once ? 2 : 0) | (hot ? 16 : 0), a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     int64_t quads = ((int64_t)a.M * a.N) / 4;
@@ -708,7 +739,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         head.M = M1;
         tail.M = a.M - M1;
         size_t esz = a.dtype == DT_BF16 ? 2 : 4, osz = a.out_mode == OUT_T ? esz : 4;
-        tail.A = (const char*)a.A + (size_t)M1 * a.K * esz;
+        tail.A = (const char*)a.A + (size_t)M1 * (a.lda ? a.lda : a.K) * esz;
         tail.out = (char*)a.out + (size_t)M1 * a.N * osz;
         hipError_t e = launch_gemm(head, s);
         return e != hipSuccess ? e : launch_gemm(tail, s);
@@ -727,12 +758,12 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         return hipGetLastError();
     }
     switch (p.cfg) {
-        case C64x256: return launch_tile<64, 256, 32, 64, 3>(a, p, s);
-        case C128x256: return launch_tile<128, 256, 64, 64, 3>(a, p, s);
-        case C256x256: return launch_tile<256, 256, 128, 64, 2>(a, p, s);
-        case C64x128: return launch_tile<64, 128, 32, 64, 4>(a, p, s);
-        case C128x128: return launch_tile<128, 128, 64, 64, 3>(a, p, s);
-        default: return launch_tile<256, 128, 64, 64, 3>(a, p, s);
+        case C64x256: return launch_tile<64, 256, 32, 64, 3>(a, p, C64x256, s);
+        case C128x256: return launch_tile<128, 256, 64, 64, 3>(a, p, C128x256, s);
+        case C256x256: return launch_tile<256, 256, 128, 64, 2>(a, p, C256x256, s);
+        case C64x128: return launch_tile<64, 128, 32, 64, 4>(a, p, C64x128, s);
+        case C128x128: return launch_tile<128, 128, 64, 64, 3>(a, p, C128x128, s);
+        default: return launch_tile<256, 128, 64, 64, 3>(a, p, C256x128, s);
     }
 }
 

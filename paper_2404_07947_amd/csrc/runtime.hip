@@ -9,6 +9,7 @@
 #include <chrono>
 #include <cmath>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -586,6 +587,7 @@ struct EncodeDesc {
     int n_tiles;
     int32_t* table = nullptr;   // paged pool: block table [n][table_w]
     int table_w = 0;
+    int max_len = 0;            // longest sequence of the batch
 };
 
 // One encode (prefill) layer over T packed tokens of n sequences.  parts: bit 0 = everything but the
@@ -612,6 +614,7 @@ static int encode_layer(exe_model* m, const DecLayerW& L, int layer, int n, int 
     if (parts & 2) {
         AttnPackedArgs a{c.dtype, T, c.n_heads, c.head_dim, n, m->qkv, d.tok_b, d.tok_pos, d.cu, encdec ? 0 : 1,
                          attn_scale(m), encdec ? m->bias_enc : nullptr, m->radius, m->ctx, d.tiles, d.n_tiles, 0};
+        a.max_len = d.max_len;
         LAUNCH(m, EXE_K_PREFILL_ATTN, attn_bytes, attn_flops, launch_attn_packed(a, m->stream));
     }
     if (parts & 1) {
@@ -648,7 +651,7 @@ static void fill_encode_desc(exe_model* m, Stager& st, EncodeDesc& d, int n, con
 {
     bool encdec = m->c.arch == EXE_ARCH_ENC_DEC;
     int T = 0;
-    for (int L : lens) T += L;
+    for (int L : lens) { T += L; d.max_len = std::max(d.max_len, L); }
     int32_t* h_tok = st.take<int32_t>(T, &d.tok);
     int32_t* h_tb = st.take<int32_t>(T, &d.tok_b);
     int32_t* h_tp = st.take<int32_t>(T, &d.tok_pos);
@@ -1450,8 +1453,13 @@ extern "C" int exe_profile(exe_model_t* m, int32_t phase, const int32_t* batch_s
                     if (lens[i] < 1) lens[i] = 1;
                 }
             }
+            // a learned position table has max_pos rows: an input of max_pos tokens, and a decode step whose K/V
+            // length after the append is max_pos, are its longest valid cases; ragged draws are clipped to that,
+            // a uniform length beyond it is an error (the row would otherwise carry a length that did not run)
+            if (learned && Lm > m->c.max_pos)
+                return fail(EXE_ERR_BAD_LENGTH, "profile length %d exceeds max_pos %d", Lm, m->c.max_pos);
             if (learned)
-                for (int& L : lens) L = std::min(L, m->c.max_pos - 1);
+                for (int& L : lens) L = std::min(L, m->c.max_pos);
             exe_profile_row_t* row = &rows[*n_rows];
             memset(row, 0, sizeof(*row));
             row->phase = phase; row->batch = B; row->length = Lm; row->ragged = ragged ? 1 : 0;
@@ -1498,7 +1506,6 @@ extern "C" int exe_run_rra(exe_model_t* m, const exe_rra_config_t* cfg, int32_t 
     std::vector<double> t_admit(n_requests, 0.0), t_finish(n_requests, 0.0);
     memset(stats, 0, sizeof(*stats));
     int next_req = 0, finished = 0, live = 0;
-    int completed_since_encode = BD;      // the first encoding phase fills the whole decode batch
     double batch_sum = 0;
     double t0 = now_s();
 
@@ -1516,19 +1523,20 @@ extern "C" int exe_run_rra(exe_model_t* m, const exe_rra_config_t* cfg, int32_t 
         if (slots.empty()) return EXE_OK;
         int r = exe_seq_release(m, (int)slots.size(), slots.data());
         if (r) return r;
-        for (int s : slots) { slot_req[s] = -1; free_slots.push_back(s); --live; ++finished; ++completed_since_encode; }
+        for (int s : slots) { slot_req[s] = -1; free_slots.push_back(s); --live; ++finished; }
         return EXE_OK;
     };
 
     std::vector<int32_t> ids, lens, res, toks, kv, nxt;
     while (finished < n_requests) {
-        // ---- encoding phase: B_E = queries completed during the previous decoding phase
-        int want = std::min(completed_since_encode, BD - live);
-        want = std::min(want, n_requests - next_req);
+        // ---- encoding phase: B_E = the queries completed since the decode batch was last full, i.e. its free
+        // slots.  When every phase admits all it asks for, that is the number completed during the previous decoding
+        // phase (Section 4); a phase cut short (workload adjustment below, or a full K/V pool) leaves its remainder
+        // to the next phase, whose B_E is raised accordingly, so the decode batch returns to B_D (Section 5).
+        int want = std::min(BD - live, n_requests - next_req);
         double budget = cfg->adjust ? (1.0 + cfg->workload_tolerance) * std::max(1, want) * mean_in : 1e300;
         double taken = 0;
         if (want > 0) stats->encode_phases += 1;
-        completed_since_encode = 0;
         while (want > 0) {
             ids.clear(); lens.clear(); res.clear();
             int64_t first_tok = tok_off[next_req], T = 0;
@@ -1577,8 +1585,7 @@ extern "C" int exe_run_rra(exe_model_t* m, const exe_rra_config_t* cfg, int32_t 
         }
         if (live == 0) {
             if (next_req >= n_requests) break;
-            completed_since_encode = BD;                      // nothing to decode: go straight to the next encoding phase
-            continue;
+            continue;                                         // nothing to decode: go straight to the next encoding phase
         }
         // ---- decoding phase: N_D iterations over the live batch
         for (int it = 0; it < cfg->n_decode && live > 0; ++it) {
@@ -1638,6 +1645,41 @@ extern "C" int exe_op_gemm(void* hip_stream, int32_t dtype, int32_t M, int32_t N
     return EXE_OK;
 }
 
+extern "C" int exe_op_gemm_plan(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t* route, int32_t* cfg, int32_t* splits,
+                                int32_t* rows_first)
+{
+    if (M < 1 || N < 1 || K < 1 || !route || !cfg || !splits || !rows_first) return fail(EXE_ERR_ARG, "bad gemm plan arguments");
+    gemm_plan_info(dtype, M, N, K, route, cfg, splits, rows_first);
+    return EXE_OK;
+}
+
+extern "C" int exe_op_paged_index_check(int32_t dtype, int32_t dh, int32_t block_size, int32_t n_waves, int32_t len)
+{
+    int shift = 0;
+    while ((1 << shift) < block_size) ++shift;
+    if ((dtype != DT_F32 && dtype != DT_BF16) || (dh != 64 && dh != 128) || block_size < 8 || block_size > 4096 ||
+        (1 << shift) != block_size || (n_waves != 4 && n_waves != 16) || len < 1)
+        return fail(EXE_ERR_ARG, "bad paged index check arguments");
+    return paged_index_check(dtype, dh, shift, n_waves, len);
+}
+
+extern "C" int exe_op_gemm_ld(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void* A, int32_t lda,
+                              const void* W, int32_t ldw, const void* bias, int32_t act, float alpha, int32_t out_mode,
+                              void* out, void* workspace, uint64_t workspace_bytes)
+{
+    if (M < 0 || N < 1 || K < 1 || !A || !W || !out) return fail(EXE_ERR_ARG, "bad gemm arguments");
+    if (dtype != DT_BF16) return fail(EXE_ERR_ARG, "strided rows are a bf16 feature");
+    if (out_mode < 0 || out_mode > 2) return fail(EXE_ERR_ARG, "bad out_mode");
+    if (K % 64 || N % 4 || lda < K || ldw < K || lda % 8 || ldw % 8) return fail(EXE_ERR_SHAPE, "K must be a multiple of 64, N of 4, strides of 8 and >= K");
+    if (gemm_route(dtype, M, N, K) != 0) return fail(EXE_ERR_SHAPE, "shape not served by the tile kernel");
+    if (gemm_workspace_bytes(dtype, M, N, K) > workspace_bytes) return fail(EXE_ERR_ARG, "workspace too small");
+    GemmArgs g{dtype, M, N, K, A, W, bias, act, alpha, out_mode, out, (float*)workspace, (size_t)workspace_bytes};
+    g.lda = lda;
+    g.ldw = ldw;
+    HIP_TRY(launch_gemm(g, (hipStream_t)hip_stream));
+    return EXE_OK;
+}
+
 extern "C" int exe_op_norm(void* hip_stream, int32_t dtype, int32_t rms, const float* x, const int32_t* row_index,
                            int32_t rows, int32_t d, const void* gain, const void* shift, float eps, float out_scale,
                            void* out)
@@ -1658,9 +1700,11 @@ extern "C" int exe_op_prefill_attention(void* hip_stream, int32_t dtype, int32_t
     std::vector<int32_t> host;
     std::vector<std::pair<int, std::pair<int, int>>> tl;
     host.resize((size_t)2 * T + n_seqs + 1);
+    int max_len = 0;
     for (int i = 0; i < n_seqs; ++i) {
         int L = cu_seqlens[i + 1] - cu_seqlens[i];
         if (L < 1) return fail(EXE_ERR_BAD_LENGTH, "empty sequence");
+        max_len = std::max(max_len, L);
         for (int p = 0; p < L; ++p) { host[cu_seqlens[i] + p] = i; host[T + cu_seqlens[i] + p] = p; }
         for (int q0 = 0; q0 < L; q0 += PREFILL_TILE_Q) tl.push_back({causal ? std::min(L, q0 + PREFILL_TILE_Q) : L, {i, q0}});
     }
@@ -1673,6 +1717,7 @@ extern "C" int exe_op_prefill_attention(void* hip_stream, int32_t dtype, int32_t
     if (e == hipSuccess) {
         AttnPackedArgs a{dtype, T, H, dh, n_seqs, qkv, dev, dev + T, dev + 2 * T, causal, scale, bias_by_dist, bias_radius,
                          out, dev + 2 * T + n_seqs + 1, (int)tl.size(), force_generic};
+        a.max_len = max_len;
         e = launch_attn_packed(a, s);
     }
     hipError_t e2 = hipStreamSynchronize(s);

@@ -197,7 +197,7 @@ int prepare_rra(const exe_sim_table_t* table, const double* p_in, int in_max, co
     x.in = Dist{p_in, in_max};
     x.out = Dist{p_out, out_max};
     x.mean_in = x.in.mean();
-    x.ctx = x.mean_in + x.out.second() / (2.0 * x.out.mean());
+    x.ctx = x.mean_in + x.out.second() / (2.0 * x.out.mean()) + 0.5;
     return EXE_OK;
 }
 

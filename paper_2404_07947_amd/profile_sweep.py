@@ -30,8 +30,8 @@ def main():
     m = exe.Model(cfg, weights)
     rows = []
     rows += m.profile(0, [1, 2, 4, 8, 16, 32], [512], n_steps=args.steps)
-    rows += m.profile(1, [1, 8, 32, 128, 512, 1024], [256, 1024, 2040], n_steps=args.steps)
-    rows += m.profile(1, [1, 8, 32, 128, 512, 1024], [1024], dist=LengthDist(1, 0.0, 256.0, 64, 2040, 20240431),
+    rows += m.profile(1, [1, 8, 32, 128, 512, 1024], [256, 1024, 2048], n_steps=args.steps)
+    rows += m.profile(1, [1, 8, 32, 128, 512, 1024], [1024], dist=LengthDist(1, 0.0, 256.0, 64, 2048, 20240431),
                       n_steps=args.steps)
     for r in rows:
         r["full_step_ms_40_layers"] = 40 * (r["attn_ms_per_layer"] + r["rest_ms_per_layer"]) + r["head_ms"]

@@ -20,14 +20,6 @@ import time
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 
-def clipped_normal_pmf(mean, std, lo, hi):
-    import numpy as np
-    s = np.arange(1, hi + 1, dtype=np.float64)
-    p = np.exp(-0.5 * ((s - mean) / std) ** 2)
-    p[: lo - 1] = 0.0
-    return p / p.sum()
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=40)
@@ -58,8 +50,8 @@ def main():
     rows += m.profile(1, [1, 8, 32, 64, 128, 192, 256], [256, 640, 1024], n_steps=args.steps)
     print(f"[schedule] profiled {len(rows)} table rows in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
     table = exe.make_sim_table(rows, shape.n_layers, shape.n_layers)
-    p_in = clipped_normal_pmf(512, 128, 64, 1024)
-    p_out = clipped_normal_pmf(128, 32, 16, 256)
+    p_in = wl.clipped_normal_pmf(512, 128, 64, 1024)
+    p_out = wl.clipped_normal_pmf(128, 32, 16, 256)
     latency_len = 200
     results = []
     for bound_s in [float(x) for x in args.bounds.split(",")]:

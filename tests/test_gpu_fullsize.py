@@ -2,6 +2,7 @@
 model, the bench job's 256 sequences encoded in 8 batches of 32, then decode iterations at batch 256.
 The oracle cannot run the whole job, so it computes the sampled sequences (the two shortest of the job) one
 by one through all 40 layers; their logits must match to the stated bar (max-norm relative error <= 2e-2).
+The job's longest sequence (>= 900 tokens) is checked too, inside its encode batch of 32, two layers deep.
 Properties that hold at any size are checked on top: every returned token is the argmax of its logits row,
 lengths advance by one per step, and a sampled sequence's logits do not depend on its batch-mates beyond
 the rounding differences of the batch-size-dependent GEMM tiling."""
@@ -78,3 +79,39 @@ def test_opt13b_full_size_sampled_sequences():
     m.encode([0], [job.in_len[i]], job.seq_tokens(i), out_device=alone)
     assert row_relerr(alone.cpu().numpy(), got_enc[i][None]) < 1e-2
     m.close()
+
+    # A long sequence (the job's longest, >= 900 tokens: 8 query tiles against up to 16 key tiles in the prefill
+    # kernel, K/V rows beyond 1000 in decode attention) inside its own encode batch of 32 at full width.  The oracle
+    # cannot take 1000 tokens through 40 layers in reasonable time, so both sides run the model's first two layers
+    # (the same tensors: weights are seeded by name) plus the final norm and LM head.
+    s2 = shape.replace(n_layers=2)
+    names = [n for n, _, _ in wl.weight_specs(shape)]
+    w2 = [weights[names.index(n)] for n, _, _ in wl.weight_specs(s2)]
+    long_i = int(np.argmax(job.in_len))
+    assert job.in_len[long_i] >= 900, job.in_len[long_i]
+    b0 = long_i // 32 * 32
+    sl = slice(b0, b0 + 32)
+    need2 = int(((job.in_len[sl] + 16 + 8) // 8 * 8).sum())
+    cfg2 = exe.config_from_shape(s2, kv_pool_bytes=need2 * s2.n_layers * 2 * s2.inner * 2, max_seqs=32,
+                                 max_batch_tokens=32 * 1024, max_batch_seqs=32)
+    m2 = exe.Model(cfg2, w2)
+    ids2 = np.arange(32, dtype=np.int32)
+    lg2 = torch.zeros((32, shape.vocab), dtype=torch.float32, device=DEV)
+    first2 = m2.encode(ids2, job.in_len[sl], job.tokens[off[b0]:off[b0 + 32]], reserve_lengths=job.in_len[sl] + 16, out_device=lg2)
+    got2 = lg2.cpu().numpy()
+    o2 = oracle.Oracle(s2, [w.float().cpu() for w in w2], "float", max_seqs=2)
+    t, lg = o2.encode(0, job.seq_tokens(long_i))
+    worst2 = row_relerr(got2[long_i - b0][None], lg[None])
+    print(f"long sequence ({int(job.in_len[long_i])} tokens, 2 layers deep) encode parity {worst2:.4f}, {time.time() - t0:.1f} s", flush=True)
+    assert worst2 < 2e-2
+    cur2 = first2.copy()
+    cur2[long_i - b0] = t
+    for step in (1, 2):
+        nxt2 = m2.decode_step(ids2, cur2, job.in_len[sl] + step, out_device=lg2)
+        t, lg = o2.decode(0, int(cur2[long_i - b0]))
+        worst2 = max(worst2, row_relerr(lg2.cpu().numpy()[long_i - b0][None], lg[None]))
+        nxt2[long_i - b0] = t
+        cur2 = nxt2
+    print(f"long sequence decode parity worst {worst2:.4f}, {time.time() - t0:.1f} s", flush=True)
+    assert worst2 < 2e-2
+    m2.close()

@@ -135,6 +135,40 @@ def test_gpt3_share_hidden_in_hidden_out():
     m.close()
 
 
+def test_gpt3_share_full_width_one_layer():
+    """configs[3] at its own width (paper Table 1: GPT-3 175B, hidden 12288, 96 heads; FFN 49152, GELU), one of the
+    share's 12 layers, hidden states in and out: 20 input tokens in two sequences, then two decode steps, against
+    the float oracle.  Every projection runs at K = 12288 / 49152 and N = 36864 / 12288 / 49152."""
+    if torch.cuda.get_device_properties(0).total_memory < 64e9:
+        pytest.skip("needs 64 GB of device memory")
+    shape = wl.gpt3_175b_share_shape(1)
+    assert (shape.d_model, shape.n_heads, shape.head_dim, shape.d_ff) == (12288, 96, 128, 49152)
+    m, o, _ = make_pair(shape, 8, "float", pool_tokens=256, max_seqs=4, max_batch_tokens=64, max_batch_seqs=4, gen_device=DEV)
+    lens = [7, 13]
+    T = sum(lens)
+    x = wl.random_hidden(83, T, shape.d_model, shape.dtype)
+    out = torch.zeros((T, shape.d_model), dtype=tdtype(shape), device=DEV)
+    print("encode gpt3 share, full width", flush=True)
+    m.encode([0, 1], lens, None, reserve_lengths=[16, 24], hidden_in=x.to(DEV), want_tokens=False, out_device=out)
+    got = out.float().cpu().numpy()
+    xs = x.float().numpy()
+    _, r0 = o.encode(0, hidden_in=xs[:7])
+    _, r1 = o.encode(1, hidden_in=xs[7:])
+    worst = max(row_relerr(got[:7], r0), row_relerr(got[7:], r1))
+    assert worst < BF16_TOL, worst
+    for step in (1, 2):
+        x2 = wl.random_hidden(83 + step, 2, shape.d_model, shape.dtype)
+        out2 = torch.zeros((2, shape.d_model), dtype=tdtype(shape), device=DEV)
+        m.decode_step([1, 0], None, [13 + step, 7 + step], hidden_in=x2.to(DEV), want_tokens=False, out_device=out2)
+        _, d1 = o.decode(1, hidden_in=x2.float().numpy()[0])
+        _, d0 = o.decode(0, hidden_in=x2.float().numpy()[1])
+        g2 = out2.float().cpu().numpy()
+        worst = max(worst, row_relerr(g2[0][None], d1[None]), row_relerr(g2[1][None], d0[None]))
+        assert worst < BF16_TOL, (step, worst)
+    print("gpt3 share full width worst", worst, flush=True)
+    m.close()
+
+
 def run_t5(shape, seed, in_lens, n_steps, tol, real="double"):
     n = len(in_lens)
     m, o, _ = make_pair(shape, seed, real, max_batch_tokens=max(4096, int(sum(in_lens))))

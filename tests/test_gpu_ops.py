@@ -38,47 +38,110 @@ GEMM_CASES = [
     (16, 512, 64), (70, 768, 128), (250, 8448, 192), (130, 260, 64),
     (37, 100, 72), (5, 52, 8),
 ]
+# Every output row is compared for these: one case per tile configuration with split-K (several k-tiles per part),
+# the 256 x 256 configuration without split, the 64 x 128 one without, and a launch split into whole rounds of
+# tiles plus a remainder launch.  The M index of an output element is spread over wave rows, 16-row MFMA blocks,
+# lanes and the groups of the LDS-turned epilogue, so sampled rows would leave most of that mapping unchecked.
+GEMM_EVERY_ROW = [
+    (16, 12288, 2048), (65, 20480, 2048), (130, 12288, 5120), (16, 2048, 512), (65, 8192, 2048), (130, 5120, 5120),
+    (1100, 1024, 512), (4099, 3072, 256), (300, 8192, 64), (16, 512, 128), (2070, 8192, 256),
+]
+# configs[3] (GPT-3-175B share: d 12288, FFN 49152, QKV 36864): its K and N
+GEMM_GPT3 = [(20, 36864, 12288), (20, 12288, 12288), (20, 49152, 12288), (20, 12288, 49152), (300, 49152, 12288)]
+_ref_cache = {}
 
 
-@pytest.mark.parametrize("M,N,K", GEMM_CASES)
-@pytest.mark.parametrize("mode", ["act_relu", "act_gelu", "resid", "f32"])
-def test_gemm_bf16(M, N, K, mode):
-    if mode != "act_relu" and (M, N, K) in [(64, 15360, 5120), (50, 50272, 512), (4099, 3072, 256), (2100, 8192, 2048)]:
-        pytest.skip("large shapes run once")
-    print(f"gemm bf16 M={M} N={N} K={K} mode={mode} route={exe.lib().exe_op_gemm_workspace(BF16, M, N, K)}", flush=True)
-    A = rnd((M, K), 1, 1.0)
-    W = rnd((N, K), 2, 0.05)
-    b = rnd((N,), 3, 0.5)
+def gemm_inputs(M, N, K):
+    return rnd((M, K), 1, 1.0), rnd((N, K), 2, 0.05), rnd((N,), 3, 0.5)
+
+
+def gemm_reference(M, N, K, rows):
+    """A[rows] . W^T in double by the oracle's linear primitive, without bias (cached: the four epilogue modes share it)."""
+    key = (M, N, K, tuple(rows))
+    if key not in _ref_cache:
+        _ref_cache.clear()                                # one shape at a time: the matrices are large
+        A, W, _ = gemm_inputs(M, N, K)
+        _ref_cache[key] = prim().linear(A.float().numpy()[rows], W.float().numpy(), None)
+    return _ref_cache[key]
+
+
+def check_gemm(M, N, K, mode, rows):
+    A, W, b = gemm_inputs(M, N, K)
     Ad, Wd, bd = A.to(DEV), W.to(DEV), b.to(DEV)
     ws_bytes = exe.exe_op_gemm_workspace(BF16, M, N, K)
     ws = torch.zeros(max(ws_bytes // 4, 1), dtype=torch.float32, device=DEV)
-    rows = np.unique(np.concatenate([[0, M - 1, min(M - 1, 2047), min(M - 1, 2048)],
-                                     np.random.default_rng(M).integers(0, M, 6)]))
-    ref = prim().linear(A.float().numpy()[rows], W.float().numpy(), b.float().numpy())
+    raw = gemm_reference(M, N, K, rows)
+    bias = b.float().numpy().astype(np.float64)
     alpha = 1.0
     if mode == "act_relu" or mode == "act_gelu":
         act = 0 if mode == "act_relu" else 1
         out = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
         exe.exe_op_gemm(BF16, M, N, K, Ad, Wd, bd, act, alpha, 0, out, ws)
-        ref = prim().act(ref, act)
+        ref = prim().act(raw + bias, act)
         tol = 2.0 ** -8
     elif mode == "resid":
         h0 = rnd((M, N), 4, 1.0, torch.float32)
         out = h0.to(DEV).clone()
         exe.exe_op_gemm(BF16, M, N, K, Ad, Wd, bd, -1, alpha, 1, out, ws)
-        ref = ref + h0.numpy()[rows].astype(np.float64)
+        ref = raw + bias + h0.numpy()[rows].astype(np.float64)
         tol = 1e-5
     else:
         alpha = 0.37
-        ref = prim().linear(A.float().numpy()[rows] * 1.0, W.float().numpy(), None) * np.float64(np.float32(alpha)) \
-            + b.float().numpy().astype(np.float64)
+        ref = raw * np.float64(np.float32(alpha)) + bias
         out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
         exe.exe_op_gemm(BF16, M, N, K, Ad, Wd, bd, -1, alpha, 2, out, ws)
         tol = 1e-5
     torch.cuda.synchronize()
     got = out.float().cpu().numpy()[rows]
-    # float accumulation of K products of magnitude <= ~|a||w|: error << tol * max|ref|
-    assert relerr(got, ref) < tol, (M, N, K, mode)
+    # float accumulation of K products of magnitude <= ~|a||w|: error << tol * max|ref|; compared row by row so
+    # that a wrong row cannot hide behind a larger one
+    assert got.shape == ref.shape
+    err = np.max(np.abs(got - ref), axis=1) / np.max(np.abs(ref))
+    assert float(err.max()) < tol, (M, N, K, mode, int(err.argmax()), float(err.max()))
+
+
+def sample_rows(M):
+    return np.unique(np.concatenate([[0, M - 1, min(M - 1, 2047), min(M - 1, 2048)],
+                                     np.random.default_rng(M).integers(0, M, 6)]))
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_CASES)
+@pytest.mark.parametrize("mode", ["act_relu", "act_gelu", "resid", "f32"])
+def test_gemm_bf16(M, N, K, mode):
+    print(f"gemm bf16 M={M} N={N} K={K} mode={mode} plan={exe.exe_op_gemm_plan(BF16, M, N, K)}", flush=True)
+    check_gemm(M, N, K, mode, sample_rows(M))
+
+
+def test_gemm_every_row_cases_cover_every_instantiation():
+    """The every-row cases below reach all six tile configurations, split-K on each of them, and a launch split into
+    whole rounds plus a remainder (asked of the library's own planner, so a retuned planner cannot silently
+    leave a kernel instantiation unchecked)."""
+    plain, split, remainder = set(), set(), False
+    for (M, N, K) in GEMM_EVERY_ROW:
+        p = exe.exe_op_gemm_plan(BF16, M, N, K)
+        assert p["route"] == 0
+        (split if p["splits"] > 1 else plain).add(p["cfg"])
+        if p["rows_first"] < M:
+            remainder = True
+            q = exe.exe_op_gemm_plan(BF16, M - p["rows_first"], N, K)
+            (split if q["splits"] > 1 else plain).add(q["cfg"])
+    assert split == set(range(6)), split
+    assert {2, 3} <= plain and remainder
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_EVERY_ROW)
+@pytest.mark.parametrize("mode", ["act_relu", "act_gelu", "resid", "f32"])
+def test_gemm_bf16_every_row(M, N, K, mode):
+    print(f"gemm bf16 every row M={M} N={N} K={K} mode={mode} plan={exe.exe_op_gemm_plan(BF16, M, N, K)}", flush=True)
+    check_gemm(M, N, K, mode, np.arange(M))
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_GPT3)
+@pytest.mark.parametrize("mode", ["act_gelu", "resid"])
+def test_gemm_bf16_gpt3_share_shapes(M, N, K, mode):
+    """The projections of configs[3] at their own K and N (paper Table 1: GPT-3 175B, hidden 12288)."""
+    print(f"gemm bf16 gpt3 M={M} N={N} K={K} mode={mode} plan={exe.exe_op_gemm_plan(BF16, M, N, K)}", flush=True)
+    check_gemm(M, N, K, mode, np.arange(M) if M <= 20 else sample_rows(M))
 
 
 @pytest.mark.parametrize("M,N,K", [(4, 2048, 256), (37, 1024, 256), (100, 768, 1024), (3, 52, 24)])
@@ -168,7 +231,7 @@ def bias_table(H, R, seed):
 @pytest.mark.parametrize("use_bias", [0, 1])
 def test_decode_attention(dtype, dh, H, use_bias):
     td = torch.float32 if dtype == F32 else torch.bfloat16
-    lens = [1, 2, 63, 64, 65, 300, 1023, 17]
+    lens = [1, 2, 63, 64, 65, 300, 1023, 17, 2560, 1281]      # up to the longest K/V of configs[3] (2048 + 512)
     B = len(lens)
     caps = [((L + 9) // 8) * 8 for L in lens]
     offs, tot = [], 0
@@ -206,8 +269,19 @@ def test_decode_attention(dtype, dh, H, use_bias):
     assert worst < (1e-5 if dtype == F32 else 2.0 ** -7), worst
 
 
-@pytest.mark.parametrize("dtype,dh,H", [(BF16, 128, 5), (F32, 64, 3)])
-@pytest.mark.parametrize("block_size", [8, 64, 256])
+def test_paged_index_replay_on_the_host():
+    """The paged kernel's row indexing, replayed on the host through the kernel's own index functions: for every
+    instantiation (type, head size), block size and launch shape, every row read lies in the block its look-up names
+    and every cached row is read exactly once.  (bf16 with head size 64 reads 16 rows per step, two blocks of 8.)"""
+    for dtype, dh in ((BF16, 64), (BF16, 128), (F32, 64), (F32, 128)):
+        for block in (8, 16, 32, 64, 256, 4096):
+            for waves in (4, 16):
+                for L in list(range(1, 300)) + [1023, 1024, 1025, 2560, 4097]:
+                    assert exe.exe_op_paged_index_check(dtype, dh, block, waves, L) == 0, (dtype, dh, block, waves, L)
+
+
+@pytest.mark.parametrize("dtype,dh,H", [(BF16, 128, 5), (F32, 64, 3), (BF16, 64, 3), (F32, 128, 2)])
+@pytest.mark.parametrize("block_size", [8, 16, 64, 256])
 @pytest.mark.parametrize("fused_append", [0, 1])
 def test_decode_attention_paged(dtype, dh, H, block_size, fused_append):
     """Block-table variant: the same rows scattered over shuffled blocks give the extent kernel's result bit for
@@ -215,7 +289,7 @@ def test_decode_attention_paged(dtype, dh, H, block_size, fused_append):
     comes from the projection output and lands in the right block."""
     # (Section 2 of the paper mentions paging of the key/value cache; the oracle is the plain attention definition)
     td = torch.float32 if dtype == F32 else torch.bfloat16
-    lens = [1, 8, 9, 63, 64, 65, 300, 1023, 17]
+    lens = [1, 8, 9, 15, 16, 17, 63, 64, 65, 300, 1023, 17, 24, 1300]
     B = len(lens)
     inner = H * dh
     nblk = [(L + block_size - 1) // block_size for L in lens]
@@ -325,3 +399,34 @@ def test_prefill_attention(dtype, dh, H, generic, causal, use_bias):
                 worst = max(worst, relerr(got[t, h * dh:(h + 1) * dh], ref))
     # bf16: probabilities are rounded to bf16 before the second product in the MFMA kernel
     assert worst < (1e-5 if dtype == F32 else 2.0 ** -6), worst
+
+
+@pytest.mark.parametrize("causal,use_bias", [(1, 0), (0, 1), (1, 1), (0, 0)])
+def test_prefill_attention_long(causal, use_bias):
+    """The MFMA kernel at the lengths the benchmarks run: 1024 (OPT-13B and T5-11B inputs, 16 key tiles) and 2048
+    (configs[3], 32 key tiles), next to a ragged 700; every row of every sequence against the oracle."""
+    H, dh = 2, 128
+    lens = [1024, 2048, 700]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    inner = H * dh
+    qkv = rnd((T, 3 * inner), 27, 1.0)
+    R = 128
+    tab = bias_table(H, R, 28) if use_bias else None
+    out = torch.zeros((T, inner), dtype=torch.bfloat16, device=DEV)
+    scale = 1.0 / np.sqrt(dh) if causal else 0.11
+    exe.exe_op_prefill_attention(BF16, cu, qkv.to(DEV), H, dh, scale, causal, None if tab is None else tab.to(DEV), R, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    x = qkv.float().numpy()
+    worst = 0.0
+    for s, L in enumerate(lens):
+        for h in range(H):
+            Ks = x[cu[s]: cu[s] + L, inner + h * dh: inner + (h + 1) * dh]
+            Vs = x[cu[s]: cu[s] + L, 2 * inner + h * dh: 2 * inner + (h + 1) * dh]
+            for i in range(L):
+                nk = i + 1 if causal else L
+                bias = tab.numpy()[h][np.clip(np.arange(nk) - i, -R, R) + R] if use_bias else None
+                ref = oracle_attention(x[cu[s] + i, h * dh:(h + 1) * dh], Ks[:nk], Vs[:nk], float(np.float32(scale)), bias)
+                worst = max(worst, relerr(got[cu[s] + i, h * dh:(h + 1) * dh], ref))
+    assert worst < 2.0 ** -6, worst

@@ -1,58 +1,16 @@
 """exe_run_rra: the RRA schedule (encode once, N_D decode iterations, refill with as many queries as completed)
 on one GPU.  Sequences are independent, so every request's tokens must equal the oracle's greedy decoding of
-that request alone; the schedule's counters must equal an independent simulation written from the paper's
-description (Section 4, "RRA Scheduling")."""
+that request alone; the schedule's counters must equal the oracle's request-by-request simulation of the schedule
+(oracle/sched_oracle.py, written from Section 4 "RRA Scheduling" and Section 5's dynamic workload adjustment)."""
 import numpy as np
 import pytest
 
 import paper_2404_07947_amd as exe
 import workload as wl
 from gpu_util import make_pair
+from oracle.sched_oracle import simulate_rra
 
 pytestmark = pytest.mark.gpu
-
-
-def simulate_rra(in_len, out_len, BD, ND):
-    """Counters of the schedule: the first encoding phase fills the decode batch; every later one admits as many
-    queries as completed since the previous one; a query produces one token at its encoding (decoder-only)
-    and one per decode iteration, and leaves when it has produced its forced output length."""
-    n = len(in_len)
-    nxt, live, finished = 0, {}, 0
-    completed = BD
-    phases = iters = batch_sum = gen = 0
-    slot = 0
-    while finished < n:
-        want = min(completed, BD - len(live), n - nxt)
-        if want > 0:
-            phases += 1
-        completed = 0
-        for _ in range(want):
-            gen += 1
-            if out_len[nxt] == 1:
-                finished += 1
-                completed += 1
-            else:
-                live[slot] = [nxt, 1]
-                slot += 1
-            nxt += 1
-        if not live:
-            if nxt >= n:
-                break
-            completed = BD
-            continue
-        for _ in range(ND):
-            if not live:
-                break
-            iters += 1
-            batch_sum += len(live)
-            for s in list(live):
-                live[s][1] += 1
-                gen += 1
-                if live[s][1] >= out_len[live[s][0]]:
-                    del live[s]
-                    finished += 1
-                    completed += 1
-    return phases, iters, batch_sum / max(iters, 1), gen
 
 
 @pytest.mark.parametrize("BD,ND,max_enc", [(4, 3, 4), (3, 1, 2), (8, 16, 3)])
@@ -77,12 +35,12 @@ def test_rra_tokens_and_counters(BD, ND, max_enc):
         o.release(0)
         want += seq
     assert got.tolist() == want
-    phases, iters, mean_b, gen = simulate_rra(in_len, out_len, BD, ND)
-    assert st["generated_tokens"] == gen == int(out_len.sum())
-    assert st["encoded_tokens"] == int(in_len.sum())
-    assert st["encode_phases"] == phases and st["decode_iterations"] == iters
-    assert abs(st["mean_decode_batch"] - mean_b) < 1e-9
-    assert st["encode_calls"] >= phases
+    sim = simulate_rra(in_len, out_len, BD, ND)
+    assert st["generated_tokens"] == sim["generated_tokens"] == int(out_len.sum())
+    assert st["encoded_tokens"] == sim["encoded_tokens"] == int(in_len.sum())
+    assert st["encode_phases"] == sim["encode_phases"] and st["decode_iterations"] == sim["decode_iterations"]
+    assert abs(st["mean_decode_batch"] - sim["mean_decode_batch"]) < 1e-9
+    assert st["encode_calls"] >= sim["encode_phases"]
     assert 0 < st["latency_p50_s"] <= st["latency_p99_s"] <= st["latency_max_s"] <= st["wall_s"]
     assert m.kv_stats()["used_bytes"] == 0 and m.kv_stats()["live_seqs"] == 0
     m.close()
@@ -101,6 +59,17 @@ def test_rra_workload_adjustment_and_errors():
     assert adj.tolist() == base.tolist()                  # the schedule never changes a sequence's tokens
     assert st1["generated_tokens"] == st0["generated_tokens"]
     assert st1["encode_phases"] >= st0["encode_phases"]   # a capped encoder workload needs at least as many phases
+    # counters against the oracle's simulation, with and without the adjustment; an encoding phase that the
+    # workload cap cut short leaves its remainder to the next phase, so the decode batch returns to B_D
+    for st, kw in ((st0, {}), (st1, {"adjust": True, "tolerance": 0.0})):
+        sim = simulate_rra(in_len, out_len, 6, 2, **kw)
+        assert st["encode_phases"] == sim["encode_phases"] and st["decode_iterations"] == sim["decode_iterations"], (st, sim)
+        assert abs(st["mean_decode_batch"] - sim["mean_decode_batch"]) < 1e-9
+    for tol in (0.1, 0.5):
+        _, st2 = m.run_rra(6, 3, in_len, out_len, toks, max_encode_batch=3, adjust=True, workload_tolerance=tol)
+        sim = simulate_rra(in_len, out_len, 6, 3, adjust=True, tolerance=tol)
+        assert st2["encode_phases"] == sim["encode_phases"] and st2["decode_iterations"] == sim["decode_iterations"]
+        assert abs(st2["mean_decode_batch"] - sim["mean_decode_batch"]) < 1e-9
     with pytest.raises(exe.ExeError) as e:
         m.run_rra(9, 2, in_len, out_len, toks, max_encode_batch=4)   # decode batch above max_batch_seqs
     assert e.value.code == -1
@@ -131,6 +100,9 @@ def test_rra_encoder_decoder():
         o.release(0)
     assert got.tolist() == want
     assert st["generated_tokens"] == int(out_len.sum())
+    sim = simulate_rra(in_len, out_len, 3, 2, decoder_only=False)
+    assert st["encode_phases"] == sim["encode_phases"] and st["decode_iterations"] == sim["decode_iterations"]
+    assert abs(st["mean_decode_batch"] - sim["mean_decode_batch"]) < 1e-9
     m.close()
 
 

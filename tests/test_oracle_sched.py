@@ -97,6 +97,62 @@ def test_exact_occupancy_is_littles_law():
     assert 1.0 / r.completed_fraction <= r.occupancy_exact + 1e-12
 
 
+def test_context_length_is_the_mean_kv_length_of_the_steady_state_queue():
+    """The length at which a decode iteration is priced, pinned by a direct simulation of the RRA queue in Section 6's
+    model (a query of S tokens is decoded for S iterations; its t-th iteration attends to its input plus t
+    positions): the mean over all (live query, iteration) pairs of the K/V length after the append.  The closed form
+    is E[S_E] + E[S (S + 1) / 2] / E[S] = E[S_E] + E[S^2] / (2 E[S]) + 1/2, whatever B_D and N_D are."""
+    p_in = normal_dist(32, 8, 8, 64)
+    p_out = normal_dist(24, 9, 2, 60)
+    enc = so.Table([1, 512], [8, 64], np.array([[1.0, 2.0], [10.0, 20.0]]))
+    dec = so.Table([1, 512], [8, 256], np.array([[1.0, 1.0], [2.0, 3.0]]))
+    r = so.rra_timeline(enc, dec, p_in, p_out, 256.0, 8, 24)
+    rng = np.random.default_rng(11)
+    in_lens, out_lens = np.arange(1, 65), np.arange(1, 61)
+    B_D, N_D = 512, 8
+    live_in = np.zeros(0, dtype=np.int64)
+    live_out = np.zeros(0, dtype=np.int64)
+    live_done = np.zeros(0, dtype=np.int64)
+    total, count = 0.0, 0
+    for phase in range(300):
+        new = B_D - live_in.size
+        live_in = np.concatenate([live_in, rng.choice(in_lens, size=new, p=p_in)])
+        live_out = np.concatenate([live_out, rng.choice(out_lens, size=new, p=p_out)])
+        live_done = np.concatenate([live_done, np.zeros(new, dtype=np.int64)])
+        for it in range(N_D):
+            live_done = live_done + 1                      # this iteration appends one position to every live query
+            if phase >= 75:
+                total += float((live_in + live_done).sum())
+                count += live_in.size
+            keep = live_done < live_out
+            live_in, live_out, live_done = live_in[keep], live_out[keep], live_done[keep]
+    assert total / count == pytest.approx(r.context_length, rel=3e-3)
+    # a single output length makes it exact: K/V lengths in+1 .. in+S, each as often as the others
+    q = np.zeros(7); q[6] = 1.0
+    one_in = np.zeros(10); one_in[9] = 1.0
+    assert so.rra_timeline(enc, dec, one_in, q, 64.0, 3, 7).context_length == pytest.approx(10 + (1 + 7) / 2)
+
+
+def test_simulate_rra_by_hand():
+    # three requests of 2 output tokens, decode batch 2, one iteration per phase: requests 0 and 1 are encoded (a
+    # token each), the one iteration finishes both; request 2 is encoded alone and finished by the next iteration
+    r = so.simulate_rra([5, 5, 5], [2, 2, 2], 2, 1)
+    assert r == {"encode_phases": 2, "decode_iterations": 2, "mean_decode_batch": 1.5, "generated_tokens": 6, "encoded_tokens": 15}
+    # encoder-decoder: no token at the encoding, so 2 iterations per request; B_D = 3 takes all three at once
+    r = so.simulate_rra([5, 5, 5], [2, 2, 2], 3, 4, decoder_only=False)
+    assert (r["encode_phases"], r["decode_iterations"], r["mean_decode_batch"], r["generated_tokens"]) == (1, 2, 3.0, 6)
+    # workload adjustment with no tolerance: 4 free slots and a mean input of 10 give a budget of 40 tokens; the
+    # inputs 30, 10 fill it, the third request (10) has to wait for the next phase, which then asks for the two
+    # slots still free plus whatever completed
+    r = so.simulate_rra([30, 10, 10, 5, 5, 5, 5, 10], [3] * 8, 4, 1, adjust=True, tolerance=0.0)
+    plain = so.simulate_rra([30, 10, 10, 5, 5, 5, 5, 10], [3] * 8, 4, 1)
+    assert r["generated_tokens"] == plain["generated_tokens"] == 24 and r["encoded_tokens"] == 80
+    assert r["encode_phases"] > plain["encode_phases"] and r["mean_decode_batch"] < plain["mean_decode_batch"]
+    # a request with a single output token completes at its encoding and never enters the decode batch
+    r = so.simulate_rra([4, 4], [1, 3], 2, 2)
+    assert (r["decode_iterations"], r["mean_decode_batch"], r["generated_tokens"]) == (2, 1.0, 4)
+
+
 # ---------------------------------------------------------------- table look-up
 def test_table_lookup():
     t = so.Table([1, 4, 16], [10, 20], np.array([[1.0, 2.0], [3.0, 6.0], [9.0, 20.0]]))
@@ -127,7 +183,7 @@ def test_rra_timeline_by_hand():
     assert r.cycle_ms == pytest.approx(61.0)
     assert r.throughput_tok_s == pytest.approx(80.0 / 61.0 * 1e3)
     assert r.throughput_seq_s == pytest.approx(20.0 / 61.0 * 1e3)
-    assert r.context_length == pytest.approx(10 + 16 / 8)
+    assert r.context_length == pytest.approx(10 + 16 / 8 + 0.5)      # K/V lengths 11, 12, 13, 14 with equal weight
     # encoded (21), one whole cycle (61), then both iterations of its last phase (40)
     assert r.latency_ms == pytest.approx(21.0 + 61.0 + 40.0)
     # a 3-token answer: second phase, first iteration only

@@ -201,6 +201,19 @@ def clipped_normal_lengths(rng: np.random.Generator, n: int, mean: float, std: f
     return np.clip(np.rint(x), lo, hi).astype(np.int32)
 
 
+def clipped_normal_pmf(mean: float, std: float, lo: int, hi: int) -> np.ndarray:
+    """The distribution `clipped_normal_lengths` draws from, as probabilities of the lengths 1 .. hi (index s - 1):
+    a normal rounded to the nearest integer, with everything below lo piled up on lo and everything above hi on hi."""
+    from math import erf, sqrt
+    cdf = lambda x: 0.5 * (1.0 + erf((x - mean) / (std * sqrt(2.0))))
+    p = np.zeros(hi, dtype=np.float64)
+    for s in range(lo, hi + 1):
+        a = -np.inf if s == lo else s - 0.5
+        b = np.inf if s == hi else s + 0.5
+        p[s - 1] = (1.0 if b == np.inf else cdf(b)) - (0.0 if a == -np.inf else cdf(a))
+    return p
+
+
 def uniform_lengths(rng: np.random.Generator, n: int, lo: int, hi: int) -> np.ndarray:
     return rng.integers(lo, hi + 1, size=n).astype(np.int32)
 
