@@ -276,6 +276,17 @@ int exe_op_gemm(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K
                 const void* W, const void* bias, int32_t act, float alpha, int32_t out_mode, void* out,
                 void* workspace, uint64_t workspace_bytes);
 uint64_t exe_op_gemm_workspace(int32_t dtype, int32_t M, int32_t N, int32_t K);
+/* exe_op_gemm for callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the split-K partial sums live in a static device array
+ * inside the library (exe_op_gemm_noalloc_max_workspace() bytes, 64 MiB, held on every GPU the library runs on until
+ * the process ends), whose address on the current device is looked up once per device.  The call allocates
+ * nothing, on the device or through any library.  Shapes whose partial sums do not fit (exe_op_gemm_workspace(...)
+ * above the maximum) are rejected with EXE_ERR_SHAPE.  Nothing in the array needs clearing between calls (a call
+ * writes every partial sum it later reads), but all calls on one GPU share it: calls that overlap on one GPU, on
+ * different streams or from different threads, race.  Same arithmetic, kernels and results as exe_op_gemm. */
+int exe_op_gemm_noalloc(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void* A, const void* W,
+                        const void* bias, int32_t act, float alpha, int32_t out_mode, void* out);
+uint64_t exe_op_gemm_noalloc_max_workspace(void);
 /* How exe_op_gemm launches a shape (host function; lets a test assert that its cases cover every kernel
  * instantiation): *route 0 = MFMA tile kernel, 2 = plain-FMA kernel; *cfg = tile configuration (0 64x256, 1 128x256,
  * 2 256x256, 3 64x128, 4 128x128, 5 256x128 rows x features); *splits = split-K parts (> 1: float partials in the

@@ -13,7 +13,7 @@ _lib = None
 DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
     "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_seq_reserve", "exe_kv_compact", "exe_profile", "exe_run_rra", "exe_kernel_timing",
-    "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_gemm_plan", "exe_op_gemm_ld", "exe_op_paged_index_check", "exe_op_norm", "exe_op_prefill_attention",
+    "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_gemm_plan", "exe_op_gemm_ld", "exe_op_gemm_noalloc", "exe_op_gemm_noalloc_max_workspace", "exe_op_paged_index_check", "exe_op_norm", "exe_op_prefill_attention",
     "exe_op_decode_attention", "exe_op_decode_attention_paged", "exe_probe_peaks", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
     # exe_sched.h (host only)
     "exe_sim_completion", "exe_sim_step_ms", "exe_sim_rra", "exe_sim_waa", "exe_sched_search", "exe_sched_rra",
@@ -139,6 +139,8 @@ def lib():
     L.exe_op_gemm_plan.argtypes = [i32, i32, i32, i32, ip, ip, ip, ip]
     L.exe_op_gemm_ld.argtypes = [vp, i32, i32, i32, i32, vp, i32, vp, i32, vp, i32, C.c_float, i32, vp, vp, C.c_uint64]
     L.exe_op_paged_index_check.argtypes = [i32, i32, i32, i32, i32]
+    L.exe_op_gemm_noalloc.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i32, C.c_float, i32, vp]
+    L.exe_op_gemm_noalloc_max_workspace.restype = C.c_uint64
     L.exe_op_norm.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, C.c_float, C.c_float, vp]
     L.exe_op_prefill_attention.argtypes = [vp, i32, i32, ip, vp, i32, i32, C.c_float, i32, vp, i32, vp, i32]
     L.exe_op_decode_attention.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, vp, i32, vp]
@@ -347,6 +349,15 @@ def exe_op_gemm_ld(dtype, M, N, K, A, lda, W, ldw, bias, act, alpha, out_mode, o
     ptr = lambda t: t if isinstance(t, int) or t is None else t.data_ptr()
     _check(lib().exe_op_gemm_ld(_stream_ptr(stream), dtype, M, N, K, ptr(A), lda, ptr(W), ldw, _dev(bias), act, alpha,
                                 out_mode, _dev(out), _dev(workspace), ws_bytes))
+
+
+def exe_op_gemm_noalloc(dtype, M, N, K, A, W, bias, act, alpha, out_mode, out, stream=None):
+    _check(lib().exe_op_gemm_noalloc(_stream_ptr(stream), dtype, M, N, K, _dev(A), _dev(W), _dev(bias), act, alpha, out_mode,
+                                     _dev(out)))
+
+
+def exe_op_gemm_noalloc_max_workspace() -> int:
+    return int(lib().exe_op_gemm_noalloc_max_workspace())
 
 
 def exe_op_paged_index_check(dtype: int, dh: int, block_size: int, n_waves: int, length: int) -> int:

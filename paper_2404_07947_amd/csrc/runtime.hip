@@ -1645,6 +1645,56 @@ extern "C" int exe_op_gemm(void* hip_stream, int32_t dtype, int32_t M, int32_t N
     return EXE_OK;
 }
 
+// ---------------------------------------------------------------- GEMM without allocations
+// The split-K partial sums of exe_op_gemm_noalloc live in this array instead of a caller workspace.  Every GPU the
+// library runs on holds its own copy until the process ends.  In host code the array's name is only a stand-in for
+// the symbol, never a device address: the address on the current device comes from hipGetSymbolAddress, once per
+// device, and only that pointer is handed to kernels.
+#define EXE_NOALLOC_SCRATCH_BYTES (64ull << 20)
+static __device__ __align__(256) unsigned char scratch[EXE_NOALLOC_SCRATCH_BYTES];
+
+static int noalloc_scratch(void** out)
+{
+    constexpr int MAXDEV = 64;
+    static std::once_flag once[MAXDEV];
+    static void* ptr[MAXDEV];
+    static hipError_t err[MAXDEV];
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAXDEV) return fail(EXE_ERR_ARG, "device %d is beyond the %d this entry point serves", dev, MAXDEV);
+    std::call_once(once[dev], [&]() {
+        void* p = nullptr;
+        err[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        ptr[dev] = err[dev] == hipSuccess ? p : nullptr;
+    });
+    if (err[dev] != hipSuccess || !ptr[dev]) return fail(EXE_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(err[dev]));
+    *out = ptr[dev];
+    return EXE_OK;
+}
+
+extern "C" uint64_t exe_op_gemm_noalloc_max_workspace(void) { return EXE_NOALLOC_SCRATCH_BYTES; }
+
+extern "C" int exe_op_gemm_noalloc(void* hip_stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void* A,
+                                   const void* W, const void* bias, int32_t act, float alpha, int32_t out_mode, void* out)
+{
+    if (M < 0 || N < 1 || K < 1 || !A || !W || !out) return fail(EXE_ERR_ARG, "bad gemm arguments");
+    if (dtype != DT_F32 && dtype != DT_BF16) return fail(EXE_ERR_ARG, "bad dtype");
+    if (out_mode < 0 || out_mode > 2) return fail(EXE_ERR_ARG, "bad out_mode");
+    if (K % 8 || N % 4) return fail(EXE_ERR_SHAPE, "K must be a multiple of 8 and N of 4");
+    size_t need = gemm_workspace_bytes(dtype, M, N, K);
+    if (need > EXE_NOALLOC_SCRATCH_BYTES)
+        return fail(EXE_ERR_SHAPE, "this shape's split-K partial sums take %llu bytes, the static scratch holds %llu",
+                    (unsigned long long)need, (unsigned long long)EXE_NOALLOC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    int r = noalloc_scratch(&ws);
+    if (r) return r;
+    // every partial sum that the reduction reads is written by the GEMM launch before it, so nothing left in the
+    // array by an earlier call is ever read and nothing needs clearing
+    GemmArgs g{dtype, M, N, K, A, W, bias, act, alpha, out_mode, out, (float*)ws, (size_t)EXE_NOALLOC_SCRATCH_BYTES};
+    HIP_TRY(launch_gemm(g, (hipStream_t)hip_stream));
+    return EXE_OK;
+}
+
 extern "C" int exe_op_gemm_plan(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t* route, int32_t* cfg, int32_t* splits,
                                 int32_t* rows_first)
 {
