@@ -90,8 +90,10 @@ def accumulate(acc, rows):
 
 
 # HBM-side bytes (rocprofv3 FETCH_SIZE x 2 + WRITE_SIZE, factors from a plain copy) per algorithmic byte, measured
-# per kernel at the OPT-13B bench shapes (profiles/traffic_opt13b_kernels.md); None = not measured
-TRAFFIC_RATIO = {"gemm_tile": 5.25, "decode_attn": 1.0, "cross_attn": 1.0, "prefill_attn": 1.64}
+# per kernel at the OPT-13B bench shapes by a separate counter run (profiles/traffic_opt13b_kernels.md gives the
+# command and the table; regenerate it whenever a kernel it covers changes).  gemm_skinny: at the job's mean decode
+# batch of 153 rows (1.20 at 64 rows, 1.51 at 256: the split-K partial sums).  A class not listed reports null.
+TRAFFIC_RATIO = {"gemm_tile": 6.04, "gemm_skinny": 1.38, "decode_attn": 1.0, "cross_attn": 1.0, "prefill_attn": 1.64}
 
 
 def roofline_entry(kind, a):
@@ -223,17 +225,20 @@ def main():
     cfg = exe.config_from_shape(shape, kv_pool_bytes=need_tokens * kv_tok, max_seqs=job.n,
                                 max_batch_tokens=job.encode_batch * max_in, max_batch_seqs=max(job.n, job.encode_batch),
                                 kv_block_size=args.kv_block)
-    stream = torch.cuda.Stream()
-    m = exe.Model(cfg, weights, stream=stream)
-    print(f"[bench] K/V pool {need_tokens * kv_tok / 1e9:.1f} GB for {job.n} sequences, {need_tokens} positions",
-          file=sys.stderr, flush=True)
     hidden = None
     if not shape.has_embed:
+        # (before the K/V pool is allocated: the generator's float temporaries are returned to the device first)
         T = int(job.in_len.sum())
         hidden = (wl.random_hidden(11, T, shape.d_model, shape.dtype, "cuda:0"),
                   wl.random_hidden(12, job.n, shape.d_model, shape.dtype, "cuda:0"),
                   torch.empty((T, shape.d_model), dtype=torch.bfloat16, device="cuda:0"),
                   torch.empty((job.n, shape.d_model), dtype=torch.bfloat16, device="cuda:0"))
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+    stream = torch.cuda.Stream()
+    m = exe.Model(cfg, weights, stream=stream)
+    print(f"[bench] K/V pool {need_tokens * kv_tok / 1e9:.1f} GB for {job.n} sequences, {need_tokens} positions",
+          file=sys.stderr, flush=True)
 
     for i in range(args.warmup):
         r = run_job(m, job, shape, hidden=hidden)

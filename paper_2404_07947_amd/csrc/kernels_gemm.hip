@@ -264,7 +264,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         int within = pid - group * GM * tiles_n;
         m0 = (first_m + within % gsz) * BM;
         n0 = (within / gsz) * BN;
-        if (flags & 16) { m0 = (pid & 1) * BM; n0 = ((pid >> 1) & 1) * BN; }
     };
     auto k_tiles = [&](int z) {
         int kbeg = z * k_per_split;
@@ -550,13 +549,12 @@ static int env_int(const char* name, int dflt)
 
 // Tuning knobs for sweeps and debugging, read from the environment once per process: EXE_GEMM_CFG forces a tile
 // configuration, EXE_GEMM_SPLIT a split count, EXE_GEMM_SPREAD the load issue pattern, EXE_GEMM_NT the
-// nontemporal weight loads, EXE_GEMM_GRID the number of persistent workgroups, EXE_GEMM_HOT makes every item work
-// on one of four tiles (all loads hit L2; wrong results, timing only).
-struct Knobs { int cfg, split, spread, nt, grid, hot; };
+// nontemporal weight loads, EXE_GEMM_GRID the number of persistent workgroups.
+struct Knobs { int cfg, split, spread, nt, grid; };
 static const Knobs& knobs()
 {
     static const Knobs k{env_int("EXE_GEMM_CFG", -1), env_int("EXE_GEMM_SPLIT", 0), env_int("EXE_GEMM_SPREAD", -1),
-                         env_int("EXE_GEMM_NT", -1), env_int("EXE_GEMM_GRID", 0), env_int("EXE_GEMM_HOT", 0)};
+                         env_int("EXE_GEMM_NT", -1), env_int("EXE_GEMM_GRID", 0)};
     return k;
 }
 
@@ -718,10 +716,9 @@ static hipError_t launch_tile(const GemmArgs& a, const Plan& p, int cfg_index, h
     int grid = items < persistent_grid() ? items : persistent_grid();
     int w_once = tm == 1 && a.M <= 64;      // measured: 7-10 % faster up to 32 rows, even from 96 rows on
     if (knobs().nt >= 0) w_once = knobs().nt != 0;
-    int hot = knobs().hot;
     kern<<<grid, threads, lds, s>>>(a.M, a.N, a.K, (const bf16_t*)a.A, (const bf16_t*)a.W, (const bf16_t*)a.bias, a.act,
                                     a.alpha, a.out_mode, a.out, a.workspace, tm, tn, p.k_per_split, p.splits,
-                                    (p.spread ? 1 : 0) | (w_once ? 2 : 0) | (hot ? 16 : 0), a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K);
+                                    (p.spread ? 1 : 0) | (w_once ? 2 : 0), a.lda ? a.lda : a.K, a.ldw ? a.ldw : a.K);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     int64_t quads = ((int64_t)a.M * a.N) / 4;

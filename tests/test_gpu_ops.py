@@ -144,6 +144,26 @@ def test_gemm_bf16_gpt3_share_shapes(M, N, K, mode):
     check_gemm(M, N, K, mode, np.arange(M) if M <= 20 else sample_rows(M))
 
 
+@pytest.mark.parametrize("M,N,K,lda,ldw", [(130, 5120, 5120, 5184, 5248), (1100, 1024, 512, 576, 520), (16, 2048, 512, 512, 640)])
+def test_gemm_bf16_padded_rows(M, N, K, lda, ldw):
+    """exe_op_gemm_ld: operands whose rows are lda / ldw elements apart (every row compared; the padding holds
+    large values that must never be read)."""
+    A = torch.full((M, lda), 1000.0, dtype=torch.bfloat16)
+    W = torch.full((N, ldw), 1000.0, dtype=torch.bfloat16)
+    A[:, :K] = rnd((M, K), 1, 1.0)
+    W[:, :K] = rnd((N, K), 2, 0.05)
+    b = rnd((N,), 3, 0.5)
+    need = exe.exe_op_gemm_workspace(BF16, M, N, K)
+    ws = torch.zeros(max(need // 4, 1), dtype=torch.float32, device=DEV)
+    out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    exe.exe_op_gemm_ld(BF16, M, N, K, A.to(DEV), lda, W.to(DEV), ldw, b.to(DEV), -1, 1.0, 2, out, ws)
+    torch.cuda.synchronize()
+    ref = prim().linear(A[:, :K].float().numpy(), W[:, :K].float().numpy(), b.float().numpy())
+    assert relerr(out.cpu().numpy(), ref) < 1e-5
+    with pytest.raises(exe.ExeError):
+        exe.exe_op_gemm_ld(BF16, M, N, K, A.to(DEV), K - 8, W.to(DEV), ldw, None, -1, 1.0, 2, out, ws)    # stride below K
+
+
 @pytest.mark.parametrize("M,N,K", [(4, 2048, 256), (37, 1024, 256), (100, 768, 1024), (3, 52, 24)])
 def test_gemm_f32(M, N, K):
     A = rnd((M, K), 5, 1.0, torch.float32)
