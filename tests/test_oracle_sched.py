@@ -167,6 +167,27 @@ def test_table_lookup():
     assert t.time_ms(0, 10) == 0.0
 
 
+def test_table_lookup_reproduces_a_cost_that_is_proportional_to_the_batch():
+    # A step whose time is c * batch * (1 + length / 100) (every sequence costs the same, no fixed cost) is bilinear
+    # in (batch, length), so interpolation inside the grid is exact; and because it is proportional to the batch,
+    # a look-up outside the profiled batches must still return it: the per-sequence cost measured at the nearest
+    # profiled batch carries over (no look-up that clamps the batch, or extrapolates the last segment of a table
+    # with an intercept, does).  The throughput batch / time is then the same at every batch, profiled or not.
+    batches, lengths = [4, 16, 64], [128, 512, 2048]
+    cost = lambda b, l: 0.03 * b * (1 + l / 100.0)
+    t = so.Table(batches, lengths, np.array([[cost(b, l) for l in lengths] for b in batches]))
+    for b in (0.25, 1, 3, 4, 9.5, 64, 65, 200, 1000):
+        for l in (128, 300, 512, 1999, 2048):
+            assert t.time_ms(b, l) == pytest.approx(cost(b, l), rel=1e-12)
+            assert b / t.time_ms(b, l) == pytest.approx(4 / t.time_ms(4, l), rel=1e-12)
+    # with a fixed cost per step in the table the look-up below the grid keeps the smallest profiled batch's
+    # per-sequence time, i.e. a batch half as large takes half as long and gains no throughput
+    u = so.Table([8, 32], [100], np.array([[5.0 + 8], [5.0 + 32]]))
+    assert u.time_ms(4, 100) == pytest.approx(0.5 * u.time_ms(8, 100))
+    assert u.time_ms(64, 100) == pytest.approx(2.0 * u.time_ms(32, 100))
+    assert u.time_ms(8, 100) == pytest.approx(13.0) and u.time_ms(7.999, 100) == pytest.approx(13.0, rel=1e-3)
+
+
 # ---------------------------------------------------------------- timeline by hand
 def test_rra_timeline_by_hand():
     # every input has 10 tokens, every output 4; N_D = 2: a query stays 2 phases and completes at U = 2, so
