@@ -10,7 +10,7 @@ import torch
 
 import paper_2404_07947_amd as exe
 import workload as wl
-from gpu_util import DEV, kv_bytes_per_token, make_pair, row_relerr
+from gpu_util import DEV, kv_bytes_per_token, make_pair, row_relerr, tdtype
 
 pytestmark = pytest.mark.gpu
 F32_TOL = 1e-4             # float model: float accumulation order only
@@ -19,9 +19,13 @@ OOM = -3
 
 
 class Trace:
-    def __init__(self, seed, kv_block_size, pool_tokens, n_ops, bf16=False):
+    def __init__(self, seed, kv_block_size, pool_tokens, n_ops, bf16=False, encdec=False):
         self.shape = wl.tiny_shape()
         self.max_in, self.max_more, self.tol = 24, 24, F32_TOL
+        self.encdec = encdec
+        if encdec:             # encoder-decoder: the input's cross-attention entries and the output's own, both in extents
+            self.shape = wl.small_t5_shape(wl.DTYPE_F32)
+            self.max_in, self.max_more = 60, 16
         if bf16:               # 3 layers, heads of 64, MFMA GEMMs, inputs long enough for several key tiles
             self.shape = self.shape.replace(name="small_bf16", dtype=wl.DTYPE_BF16, max_pos=512, n_layers=3)
             self.max_in, self.max_more, self.tol = 150, 40, BF16_TOL
@@ -29,7 +33,7 @@ class Trace:
         self.m, self.o, _ = make_pair(self.shape, wl.BASE_SEED + 7, "double", pool_tokens=pool_tokens, max_seqs=64,
                                       max_batch_tokens=512, max_batch_seqs=16, kv_block_size=kv_block_size)
         self.rng = np.random.default_rng(seed)
-        self.live = {}                     # library id -> dict(oid, len, cur, reserve)
+        self.live = {}                     # library id -> dict(oid, len, cur, reserve, n_in); len = K/V rows of the decoder
         self.next_oid = 0
         self.free_oids = []
         self.worst = 0.0
@@ -73,13 +77,18 @@ class Trace:
             if i not in ids:
                 ids.append(i)
         lens = self.rng.integers(1, self.max_in + 1, size=k)
-        reserve = np.minimum(self.shape.max_pos, lens + self.rng.integers(1, self.max_more + 1, size=k))
+        more = self.rng.integers(1, self.max_more + 1, size=k)
+        reserve = more if self.encdec else np.minimum(self.shape.max_pos, lens + more)
         toks = wl.random_tokens(self.rng, int(lens.sum()), self.shape.vocab)
-        logits = torch.zeros((k, self.shape.vocab), dtype=torch.float32, device=DEV)
+        if self.encdec:                    # the call returns the encoder's output rows
+            logits = torch.zeros((int(lens.sum()), self.shape.d_model), dtype=tdtype(self.shape), device=DEV)
+        else:
+            logits = torch.zeros((k, self.shape.vocab), dtype=torch.float32, device=DEV)
         for attempt in range(4):
             before = self.m.kv_stats()
             try:
-                self.m.encode(ids, lens, toks, reserve_lengths=None if self.paged else reserve, out_device=logits)
+                self.m.encode(ids, lens, toks, reserve_lengths=None if self.paged else reserve,
+                              want_tokens=not self.encdec, out_device=logits)
                 break
             except exe.ExeError as e:
                 assert e.code == OOM, e
@@ -93,19 +102,26 @@ class Trace:
                     raise
         else:
             return
-        got = logits.cpu().numpy()
+        got = logits.float().cpu().numpy()
         off = np.concatenate([[0], np.cumsum(lens)])
         refs = []
         for j, i in enumerate(ids):
             oid = self.take_oid()
             t, lg = self.o.encode(oid, toks[off[j]:off[j + 1]])
             refs.append(lg)
-            self.live[i] = {"oid": oid, "len": int(lens[j]), "cur": int(t), "reserve": int(reserve[j])}
-        self.check_rows(got, refs, "admit")
+            self.live[i] = {"oid": oid, "len": 0 if self.encdec else int(lens[j]), "cur": 0 if self.encdec else int(t),
+                            "reserve": int(reserve[j]), "n_in": int(lens[j])}
+        if self.encdec:
+            got, refs = [got[off[j]:off[j + 1]] for j in range(k)], refs
+            for g, r in zip(got, refs):
+                self.worst = max(self.worst, row_relerr(g, r))
+            assert self.worst < self.tol, ("encoder output", self.worst)
+        else:
+            self.check_rows(got, refs, "admit")
         self.counts["admit"] += 1
 
     def step(self):
-        limit = lambda s: self.shape.max_pos if self.paged else s["reserve"]
+        limit = lambda s: self.shape.max_pos if self.paged else s["reserve"]       # encoder-decoder: output rows only
         able = [i for i, s in sorted(self.live.items()) if s["len"] + 1 <= limit(s)]
         if not able:
             return
@@ -148,7 +164,8 @@ class Trace:
             return
         i = int(self.rng.choice(sorted(self.live)))
         s = self.live[i]
-        want = int(self.rng.integers(s["len"], min(self.shape.max_pos, s["len"] + 2 * self.max_more) + 1))
+        top = s["len"] + 2 * self.max_more
+        want = int(self.rng.integers(max(s["len"], 1), (top if self.encdec else min(self.shape.max_pos, top)) + 1))
         try:
             self.m.seq_reserve(i, want)
             s["reserve"] = want
@@ -173,8 +190,8 @@ class Trace:
         i = int(self.rng.choice(sorted(self.live)))
         s = self.live[i]
         buf, st = self.m.seq_export(i)
-        assert st == {"kv_len": s["len"], "cross_len": 0}
-        assert buf.nbytes == kv_bytes_per_token(self.shape) * s["len"]
+        assert st == {"kv_len": s["len"], "cross_len": s["n_in"] if self.encdec else 0}
+        assert buf.nbytes == kv_bytes_per_token(self.shape) * (s["len"] + (s["n_in"] if self.encdec else 0))
         self.m.seq_release([i])
         del self.live[i]
         j = self.free_id()
@@ -189,7 +206,7 @@ class Trace:
             assert self.m.seq_length(i) == s["len"]
         if not self.paged:
             per_token = kv_bytes_per_token(self.shape)
-            assert st["used_bytes"] >= per_token * sum(s["len"] for s in self.live.values())
+            assert st["used_bytes"] >= per_token * sum(s["len"] + (s["n_in"] if self.encdec else 0) for s in self.live.values())
 
     def run(self):
         ops = [self.admit, self.step, self.release, self.reserve, self.compact, self.move]
@@ -217,3 +234,10 @@ def test_random_serving_trace(seed, kv_block_size, pool_tokens, bf16):
     print("trace", seed, counts, flush=True)
     assert counts["admit"] >= 5 and counts["step"] >= 20 and counts["move"] >= 1
     assert counts["refused"] >= 1                    # the pool was small enough to run out
+
+
+@pytest.mark.parametrize("seed,pool_tokens", [(201, 260), (202, 400)])
+def test_random_serving_trace_encoder_decoder(seed, pool_tokens):
+    counts = Trace(seed, 0, pool_tokens, n_ops=90, encdec=True).run()
+    print("trace", seed, counts, flush=True)
+    assert counts["admit"] >= 5 and counts["step"] >= 20 and counts["move"] >= 1 and counts["refused"] >= 1
