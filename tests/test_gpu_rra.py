@@ -122,3 +122,42 @@ def test_rra_pool_pressure_defers_admission():
     assert st["mean_decode_batch"] < st2["mean_decode_batch"]      # fewer sequences fit at once
     assert m.kv_stats()["used_bytes"] == 0
     m.close(); m2.close()
+
+
+def test_rra_random_schedules_against_the_simulation():
+    """Seeded random schedules (decode batch, N_D, encode-batch cap, workload adjustment and its tolerance, request
+    mix): the counters must equal the oracle's simulation each time and the tokens never depend on the schedule."""
+    shape = wl.tiny_shape()
+    m, o, _ = make_pair(shape, wl.BASE_SEED, "float", pool_tokens=4096, max_seqs=32, max_batch_tokens=512, max_batch_seqs=12)
+    rng = np.random.default_rng(31)
+    for case in range(14):
+        n = int(rng.integers(3, 30))
+        in_len = wl.uniform_lengths(rng, n, 1, 30)
+        out_len = rng.integers(1, 12, size=n).astype(np.int32)
+        toks = wl.random_tokens(rng, int(in_len.sum()), shape.vocab)
+        BD, ND = int(rng.integers(1, 13)), int(rng.integers(1, 9))
+        max_enc = int(rng.integers(1, 13))
+        adjust = bool(rng.integers(0, 2))
+        tol = float(rng.choice([0.0, 0.1, 0.25, 1.0]))
+        print(f"case {case}: n {n} BD {BD} ND {ND} max_enc {max_enc} adjust {adjust} tol {tol}", flush=True)
+        got, st = m.run_rra(BD, ND, in_len, out_len, toks, max_encode_batch=max_enc, adjust=adjust, workload_tolerance=tol)
+        sim = simulate_rra(in_len, out_len, BD, ND, adjust=adjust, tolerance=tol)
+        assert st["generated_tokens"] == sim["generated_tokens"] == int(out_len.sum())
+        assert st["encoded_tokens"] == sim["encoded_tokens"] == int(in_len.sum())
+        assert (st["encode_phases"], st["decode_iterations"]) == (sim["encode_phases"], sim["decode_iterations"]), (st, sim)
+        assert abs(st["mean_decode_batch"] - sim["mean_decode_batch"]) < 1e-9
+        ref, _ = m.run_rra(12, 1, in_len, out_len, toks, max_encode_batch=12)      # another schedule, same tokens
+        assert got.tolist() == ref.tolist()
+        if case < 3:                                                              # and the oracle's, request by request
+            off = np.concatenate([[0], np.cumsum(in_len)])
+            want = []
+            for i in range(n):
+                t, _ = o.encode(0, toks[off[i]:off[i + 1]])
+                want.append(t)
+                for _ in range(out_len[i] - 1):
+                    t, _ = o.decode(0, t)
+                    want.append(t)
+                o.release(0)
+            assert got.tolist() == want
+        assert m.kv_stats()["used_bytes"] == 0 and m.kv_stats()["live_seqs"] == 0
+    m.close()
