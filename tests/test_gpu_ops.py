@@ -136,6 +136,29 @@ def test_gemm_bf16_every_row(M, N, K, mode):
     check_gemm(M, N, K, mode, np.arange(M))
 
 
+def random_gemm_shapes():
+    """Seeded random shapes around the planner's decision boundaries: row counts up to a few tiles, feature counts
+    that leave ragged tile columns, depths from one k-tile to many."""
+    rng = np.random.default_rng(77)
+    shapes = []
+    for _ in range(48):
+        M = int(rng.choice([rng.integers(1, 70), rng.integers(60, 270), rng.integers(250, 1300)]))
+        N = 4 * int(rng.choice([rng.integers(8, 200), rng.integers(200, 1400), rng.integers(1400, 5200)]))
+        K = 64 * int(rng.choice([rng.integers(1, 9), rng.integers(8, 40), rng.integers(40, 90)]))
+        if M * N > 3_000_000:
+            N = max(64, (3_000_000 // M) // 4 * 4)
+        if M * N * K > 6_000_000_000:                    # keeps the oracle's double-precision product to a second or two
+            K = max(64, 6_000_000_000 // (M * N) // 64 * 64)
+        shapes.append((M, N, K, ["act_relu", "act_gelu", "resid", "f32"][int(rng.integers(0, 4))]))
+    return shapes
+
+
+@pytest.mark.parametrize("M,N,K,mode", random_gemm_shapes())
+def test_gemm_bf16_random_shapes_every_row(M, N, K, mode):
+    print(f"gemm bf16 random M={M} N={N} K={K} mode={mode} plan={exe.exe_op_gemm_plan(BF16, M, N, K)}", flush=True)
+    check_gemm(M, N, K, mode, np.arange(M))
+
+
 @pytest.mark.parametrize("M,N,K", GEMM_GPT3)
 @pytest.mark.parametrize("mode", ["act_gelu", "resid"])
 def test_gemm_bf16_gpt3_share_shapes(M, N, K, mode):
@@ -450,3 +473,98 @@ def test_prefill_attention_long(causal, use_bias):
                 ref = oracle_attention(x[cu[s] + i, h * dh:(h + 1) * dh], Ks[:nk], Vs[:nk], float(np.float32(scale)), bias)
                 worst = max(worst, relerr(got[cu[s] + i, h * dh:(h + 1) * dh], ref))
     assert worst < 2.0 ** -6, worst
+
+
+def random_prefill_batches():
+    rng = np.random.default_rng(91)
+    cases = []
+    for _ in range(8):
+        n = int(rng.integers(1, 9))
+        lens = [int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), 64 * rng.integers(1, 8), 64 * rng.integers(1, 8) + 1]))
+                for _ in range(n)]
+        while sum(lens) > 1500:
+            lens.pop()
+        cases.append((tuple(lens), int(rng.integers(1, 4)), int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2**31))))
+    return cases
+
+
+@pytest.mark.parametrize("lens,H,causal,use_bias,seed", random_prefill_batches())
+def test_prefill_attention_random_batches(lens, H, causal, use_bias, seed):
+    """Seeded random ragged batches (sequence counts, lengths on and off the tile edges, heads, mask and bias) through
+    the MFMA kernel; every row of every sequence against the oracle."""
+    dh, R = 128, 128
+    lens = list(lens)
+    print(f"prefill random lens={lens} H={H} causal={causal} bias={use_bias}", flush=True)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, inner = int(cu[-1]), H * dh
+    qkv = rnd((T, 3 * inner), seed % 1000 + 100, 1.0)
+    tab = bias_table(H, R, seed % 1000 + 101) if use_bias else None
+    out = torch.zeros((T, inner), dtype=torch.bfloat16, device=DEV)
+    scale = 1.0 / np.sqrt(dh)
+    exe.exe_op_prefill_attention(BF16, cu, qkv.to(DEV), H, dh, scale, causal, None if tab is None else tab.to(DEV), R, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    x = qkv.float().numpy()
+    worst = 0.0
+    for s, L in enumerate(lens):
+        for h in range(H):
+            Ks = x[cu[s]: cu[s] + L, inner + h * dh: inner + (h + 1) * dh]
+            Vs = x[cu[s]: cu[s] + L, 2 * inner + h * dh: 2 * inner + (h + 1) * dh]
+            for i in range(L):
+                nk = i + 1 if causal else L
+                bias = tab.numpy()[h][np.clip(np.arange(nk) - i, -R, R) + R] if use_bias else None
+                ref = oracle_attention(x[cu[s] + i, h * dh:(h + 1) * dh], Ks[:nk], Vs[:nk], float(np.float32(scale)), bias)
+                worst = max(worst, relerr(got[cu[s] + i, h * dh:(h + 1) * dh], ref))
+    assert worst < 2.0 ** -6, worst
+
+
+def random_decode_batches():
+    rng = np.random.default_rng(93)
+    cases = []
+    for _ in range(10):
+        B = int(rng.integers(1, 40))
+        top = int(rng.choice([40, 330, 1500]))           # short batches take the 4-wave launch, long ones 16 waves
+        lens = tuple(int(x) for x in rng.integers(1, top + 1, size=B))
+        dtype, dh = [(BF16, 128), (BF16, 64), (F32, 64), (F32, 128)][int(rng.integers(0, 4))]
+        cases.append((lens, dtype, dh, int(rng.integers(1, 6)), int(rng.integers(0, 2)), int(rng.integers(0, 1000))))
+    return cases
+
+
+@pytest.mark.parametrize("lens,dtype,dh,H,use_bias,seed", random_decode_batches())
+def test_decode_attention_random_batches(lens, dtype, dh, H, use_bias, seed):
+    """Seeded random batches of cached lengths (both launch shapes), element types, head sizes and bias: one query row
+    per sequence against the oracle."""
+    td = torch.float32 if dtype == F32 else torch.bfloat16
+    lens = list(lens)
+    B = len(lens)
+    print(f"decode random B={B} max len {max(lens)} dtype={dtype} dh={dh} H={H} bias={use_bias}", flush=True)
+    caps = [((L + 8) // 8) * 8 for L in lens]
+    offs, tot = [], 0
+    for c in caps:
+        offs.append(tot)
+        tot += 2 * H * c * dh + 8 * int((seed + c) % 5)      # uneven gaps between extents
+    pool = rnd((tot + 64,), seed + 1, 1.0, td)
+    q = rnd((B, H * dh), seed + 2, 1.0, td)
+    R = 128
+    tab = bias_table(H, R, seed + 3) if use_bias else None
+    qpos = [L - 1 for L in lens]
+    out = torch.zeros((B, H * dh), dtype=td, device=DEV)
+    i64 = lambda a: torch.tensor(a, dtype=torch.int64, device=DEV)
+    i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=DEV)
+    scale = 1.0 / np.sqrt(dh)
+    exe.exe_op_decode_attention(dtype, B, q.to(DEV), H * dh, pool.to(DEV), i64(offs), i32(caps), i32(lens), i32(qpos),
+                                H, dh, scale, None if tab is None else tab.to(DEV), R, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    pf, qf = pool.float().numpy(), q.float().numpy()
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            kb = offs[b] + h * caps[b] * dh
+            K = pf[kb: kb + lens[b] * dh].reshape(lens[b], dh)
+            vb = offs[b] + H * caps[b] * dh + h * caps[b] * dh
+            V = pf[vb: vb + lens[b] * dh].reshape(lens[b], dh)
+            bias = tab.numpy()[h][np.clip(np.arange(lens[b]) - qpos[b], -R, R) + R] if use_bias else None
+            ref = oracle_attention(qf[b, h * dh:(h + 1) * dh], K, V, float(np.float32(scale)), bias)
+            worst = max(worst, relerr(got[b, h * dh:(h + 1) * dh], ref))
+    assert worst < (1e-5 if dtype == F32 else 2.0 ** -7), worst
