@@ -267,7 +267,7 @@ int exe_kernel_times(exe_model_t* m, exe_kernel_time_t* rows /* [EXE_K_COUNT] */
  * Tooling of this library, no part of the paper's method and citing nothing from it: the per-kernel-class timing
  * above (exe_kernel_timing, exe_kernel_times), the single-operation entry points below (exe_op_*: device pointers,
  * enqueued on `hip_stream`, NOT synchronised; they run the same kernels the model calls use, for per-kernel
- * parity tests and micro-benchmarks) and exe_probe_peaks.
+ * parity tests and micro-benchmarks), exe_probe_peaks and exe_probe_ingest.
  */
 /* out = epilogue(alpha * A[M,K] . W[N,K]^T + bias):  out_mode 0: dtype out [M,N] with activation
  * act (-1 none, EXE_ACT_*); 1: float resid [M,N] += result; 2: float out [M,N].
@@ -342,6 +342,20 @@ int exe_op_paged_index_check(int32_t dtype, int32_t dh, int32_t block_size, int3
  * freed by the call), *mfma_bf16_flops_per_s = rate of back-to-back bf16 16x16x32 MFMAs on all compute units at the
  * clock that load sustains.  Either pointer may be NULL.  Synchronises the stream; host pointers. */
 int exe_probe_peaks(void* hip_stream, uint64_t read_bytes, double* hbm_read_bytes_per_s, double* mfma_bf16_flops_per_s);
+/* Rate at which the compute units take tile data in (tooling, like exe_probe_peaks): one workgroup of `waves` waves
+ * (1, 2, 4, 8, 16) per compute unit reads a private region of region_bytes `passes` times, each wave issuing batches
+ * of loads_per_batch (2, 4, 8, 16) wave-wide 16-byte loads (1 KB each) with the batch before still in flight, so
+ * waves x loads_per_batch (at most 64) to twice that many KB are in flight per compute unit.  mode 0 = loads to
+ * registers, 1 = the same nontemporal, 2 = direct global->LDS loads (the tile loader of the GEMM and prefill
+ * kernels), 3 = the same nontemporal.  A small region with many passes stays in L2 (the L1 <-> L2 path of a compute
+ * unit); a region of megabytes with passes = 1 is a stream from HBM.  row_bytes = 0 reads the region front to back;
+ * row_bytes > 0 (modes 2 and 3, waves x loads_per_batch = 16, a multiple of 128) makes the region a panel of 128 rows
+ * of row_bytes bytes, walked 128 bytes at a time with 8 rows per wave-load, as the loader of a 128-row operand tile of a
+ * row-major matrix does (region_bytes is then 128 x row_bytes).  region_bytes must be a multiple of
+ * waves x loads_per_batch KB.  *bytes_per_s = bytes read per second over all compute units.  Allocates and frees its
+ * buffer, synchronises the stream; host pointer. */
+int exe_probe_ingest(void* hip_stream, int32_t mode, uint64_t region_bytes, int32_t passes, int32_t waves,
+                     int32_t loads_per_batch, int32_t row_bytes, double* bytes_per_s);
 /* argmax over each row of float logits [rows, n] -> int32 out [rows]; lowest index on ties */
 int exe_op_argmax(void* hip_stream, const float* logits, int32_t rows, int32_t n, int32_t* out);
 /* T5 bucket of rel = key - query as this library computes it (host function, exact integer arithmetic) */

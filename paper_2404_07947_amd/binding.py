@@ -14,7 +14,7 @@ DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
     "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_seq_reserve", "exe_kv_compact", "exe_profile", "exe_run_rra", "exe_kernel_timing",
     "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_gemm_plan", "exe_op_gemm_ld", "exe_op_gemm_noalloc", "exe_op_gemm_noalloc_max_workspace", "exe_op_paged_index_check", "exe_op_norm", "exe_op_prefill_attention",
-    "exe_op_decode_attention", "exe_op_decode_attention_paged", "exe_probe_peaks", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
+    "exe_op_decode_attention", "exe_op_decode_attention_paged", "exe_probe_peaks", "exe_probe_ingest", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
     # exe_sched.h (host only)
     "exe_sim_completion", "exe_sim_step_ms", "exe_sim_rra", "exe_sim_waa", "exe_sched_search", "exe_sched_rra",
 ]
@@ -397,6 +397,17 @@ def exe_probe_peaks(read_bytes: int = 0, stream=None) -> dict:
     r, f = C.c_double(), C.c_double()
     _check(L.exe_probe_peaks(_stream_ptr(stream), read_bytes, C.byref(r), C.byref(f)))
     return {"hbm_read_bytes_per_s": r.value, "mfma_bf16_flops_per_s": f.value}
+
+
+def exe_probe_ingest(mode: int, region_bytes: int, passes: int, waves: int, loads_per_batch: int, row_bytes: int = 0,
+                     stream=None) -> float:
+    """Bytes per second that one workgroup per compute unit takes in (see include/exe.h)."""
+    L = lib()
+    L.exe_probe_ingest.argtypes = [C.c_void_p, C.c_int32, C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                   C.POINTER(C.c_double)]
+    r = C.c_double()
+    _check(L.exe_probe_ingest(_stream_ptr(stream), mode, region_bytes, passes, waves, loads_per_batch, row_bytes, C.byref(r)))
+    return r.value
 
 
 def exe_op_argmax(logits, rows, n, out, stream=None):

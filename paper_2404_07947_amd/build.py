@@ -55,5 +55,26 @@ def build(force: bool = False, verbose: bool = True) -> str:
     return LIB
 
 
+def build_ablation(mask: int, verbose: bool = True) -> str:
+    """Builds libexe_ablate<mask>.so: the library with the tile GEMM compiled as the measurement variant
+    EXE_GEMM_ABLATE=mask (see csrc/kernels_gemm.hip; its results are meaningless, its timing isolates a part of
+    the kernel).  The other objects are the library's own."""
+    build(verbose=verbose)
+    obj = os.path.join(OBJ, f"kernels_gemm_ablate{mask}.o")
+    cmd = [HIPCC, *FLAGS, f"-DEXE_GEMM_ABLATE={mask}", "-c", os.path.join(CSRC, "kernels_gemm.hip"), "-o", obj]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l))
+    objs = [obj if src == "kernels_gemm.hip" else os.path.join(OBJ, os.path.splitext(src)[0] + ".o") for src in SOURCES]
+    lib = os.path.join(HERE, f"libexe_ablate{mask}.so")
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
+    return lib
+
+
 if __name__ == "__main__":
-    build(force="--force" in sys.argv)
+    if "--ablate" in sys.argv:
+        print(build_ablation(int(sys.argv[sys.argv.index("--ablate") + 1])))
+    else:
+        build(force="--force" in sys.argv)

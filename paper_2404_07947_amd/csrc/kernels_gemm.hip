@@ -9,6 +9,12 @@
 // Both A and W are K-contiguous, so both MFMA operands are 16-byte vectors along K.  The MFMA "A" operand
 // is fed with weight rows and the "B" operand with activation rows: the accumulator then holds 4
 // consecutive output features per lane, which makes the epilogue's loads and stores 8/16-byte vectors.
+//
+// EXE_GEMM_ABLATE (a compile-time bit mask, 0 in the library proper) builds measurement variants of the tile kernel
+// whose results are meaningless and whose timing isolates a part: bit 0 drops the MFMAs (the fragment reads from
+// LDS go with them), bit 1 drops the loads of the activation tiles, bit 2 the loads of the weight tiles.  What
+// remains keeps its waits, barriers, epilogue and split-K reduction.  `python -m paper_2404_07947_amd.build
+// --ablate N` builds libexe_ablate<N>.so beside the library.
 #include <stdlib.h>
 
 #include <mutex>
@@ -17,6 +23,10 @@
 
 #include "common.h"
 #include "kernels.h"
+
+#ifndef EXE_GEMM_ABLATE
+#define EXE_GEMM_ABLATE 0
+#endif
 
 namespace exe {
 
@@ -239,7 +249,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     constexpr int TMH = TM / MH;
     constexpr int NS = 2 * MH;                      // sub-steps per k-tile
     constexpr int A_PASSES = BM / 8 / NW, B_PASSES = BN / 8 / NW;   // 1 KB wave-loads per wave per stage
-    constexpr int LPT = A_PASSES + B_PASSES;
+    // wave-loads a wave issues per k-tile (all of them, unless a measurement variant drops an operand's)
+    constexpr int LPT = ((EXE_GEMM_ABLATE & 2) ? 0 : A_PASSES) + ((EXE_GEMM_ABLATE & 4) ? 0 : B_PASSES);
+    constexpr int LPX = A_PASSES + B_PASSES;      // positions of the issue sequence: A passes, then W passes
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "tile/waves mismatch");
     static_assert(LPT * (ST - 1) <= 63, "vmcnt range");
     extern __shared__ __align__(16) unsigned char lds[];
@@ -324,6 +336,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         const char* kw = base_w + ld_kt * (TBK * 2);
 #pragma unroll
         for (int x = decltype(x0)::value; x < decltype(x1)::value; ++x) {
+            if ((EXE_GEMM_ABLATE & 2) && x < A_PASSES) continue;
+            if ((EXE_GEMM_ABLATE & 4) && x >= A_PASSES) continue;
             if (x < A_PASSES) load_to_lds(ka, off_a[x], base + x * NW * 1024);
             else if (w_once) load_to_lds_nt(kw, off_w[x - A_PASSES], base + BM * TBK * 2 + (x - A_PASSES) * NW * 1024);
             else load_to_lds(kw, off_w[x - A_PASSES], base + BM * TBK * 2 + (x - A_PASSES) * NW * 1024);
@@ -342,12 +356,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     // A k-tile's loads are issued in four parts spread over 24 MFMAs: a burst of all of them fills the queue of
     // the CU's address unit, and a wave waiting to issue a load issues no MFMA either.
     // (`spread` = 0 issues them all at once behind the barrier.)
-    constexpr int Q1 = LPT / 4, Q2 = LPT / 2, Q3 = LPT * 3 / 4;
+    constexpr int Q1 = LPX / 4, Q2 = LPX / 2, Q3 = LPX * 3 / 4;
     using X0 = std::integral_constant<int, 0>;
     using X1 = std::integral_constant<int, Q1>;
     using X2 = std::integral_constant<int, Q2>;
     using X3 = std::integral_constant<int, Q3>;
-    using X4 = std::integral_constant<int, LPT>;
+    using X4 = std::integral_constant<int, LPX>;
 
     // MFMA operands (16x16x32): lane l holds row l%16 and the 8 k-values 8*(l/16) .. +7 of a 32-k step, i.e.
     // 16-byte chunk 4*ks + l/16 of the stage row.  The W fragments of a 32-k step are kept for all its row parts.
@@ -372,6 +386,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     auto mma = [&](int s, int half) {
         constexpr int NM = TN * TMH;
         int ks = s / MH, mh = s % MH;
+        if (EXE_GEMM_ABLATE & 1) return;
 #pragma unroll
         for (int x = 0; x < NM; ++x) {
             if ((x < NM / 2) != (half == 0)) continue;
