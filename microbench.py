@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Micro-benchmarks behind the statements in the design doc about what bounds the GEMMs (HIP-event timing, no profiler):
+"""Micro-benchmarks of what bounds the GEMMs (HIP-event timing, no profiler):
 
   python3 microbench.py ingest
       the rate at which a compute unit takes tile data in (exe_probe_ingest): L2-resident regions against the bytes in
