@@ -8,8 +8,15 @@
   python3 microbench.py decode_gemm [--rows 16,64,153,256] [--lib PATH]
       the four projections of an OPT-13B layer (QKV, out, FFN1, FFN2) at decode row counts, split-K reductions included,
       with the weights rotating through HBM-resident copies; --lib takes a measurement variant of the library built by
-      `python -m paper_2404_07947_amd.build --ablate N` (N: 1 no MFMA, 2 no activation loads, 4 no weight loads, sums
+      `python -m paper_2404_07947_amd.build --variant ablateN -DEXE_GEMM_ABLATE=N` (N: 1 no MFMA, 2 no activation loads, 4 no weight loads, sums
       combine), whose results are meaningless and whose timing isolates a part of the kernel.
+  python3 microbench.py encode_gemm [--rows 16020,16384] [--lib PATH]
+      the same four projections at encode row counts; --lib e.g. a variant with the loads of a k-tile issued later
+      or earlier (`build --variant late -DEXE_GEMM_ISSUE_AT=1`).
+  python3 microbench.py two_streams
+      one decode layer's attention and projections for the whole batch on one stream, against two half-batches on
+      one stream and on two streams (one a phase ahead, so that one half's attention could run beside the other
+      half's projections).
 """
 import argparse
 import os
@@ -84,20 +91,132 @@ def decode_gemm(rows, iters=40, copies=6):
         print(f"| {M} | " + " | ".join(cells) + f" | {layer:.1f} | {w_bytes / layer / 1e6:.2f} |", flush=True)
 
 
+def encode_gemm(rows, iters=8):
+    print("| rows | " + " | ".join(f"{n} us (TFLOP/s)" for _, _, n in OPT_GEMMS) + " | all TFLOP/s |\n|---:|" + "---:|" * 5)
+    for M in rows:
+        cells, tot, fl = [], 0.0, 0.0
+        for N, K, _ in OPT_GEMMS:
+            A = torch.randn((M, K), device=DEV).to(torch.bfloat16)
+            Ws = [(torch.randn((N, K), device=DEV) * 0.02).to(torch.bfloat16) for _ in range(2)]
+            bias = torch.randn((N,), device=DEV).to(torch.bfloat16)
+            out = torch.empty((M, N), device=DEV, dtype=torch.bfloat16)
+            ws = torch.zeros(exe.exe_op_gemm_workspace(1, M, N, K) // 4 + 16, device=DEV, dtype=torch.float32)
+            for i in range(2):
+                exe.exe_op_gemm(1, M, N, K, A, Ws[i], bias, 0, 1.0, 0, out, ws)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for i in range(iters):
+                exe.exe_op_gemm(1, M, N, K, A, Ws[i % 2], bias, 0, 1.0, 0, out, ws)
+            b.record()
+            torch.cuda.synchronize()
+            t = a.elapsed_time(b) / iters * 1e3
+            tot += t
+            fl += 2.0 * M * N * K
+            cells.append(f"{t:.1f} ({2.0 * M * N * K / t / 1e6:.0f})")
+            del A, Ws, out, ws
+        print(f"| {M} | " + " | ".join(cells) + f" | {fl / tot / 1e6:.0f} |", flush=True)
+
+
+def two_streams(layers=20):
+    import numpy as np
+    import workload as wl
+    H, dh = 40, 128
+    lens_all = (wl.workload_opt13b(256).in_len + 64).astype(np.int32)
+    shapes = [(N, K) for N, K, _ in OPT_GEMMS]
+    wsets = [[(torch.randn((N, K), device=DEV) * 0.02).to(torch.bfloat16) for N, K in shapes] for _ in range(3)]
+
+    def attention(lens):
+        lens = np.asarray(lens, dtype=np.int32)
+        B = len(lens)
+        caps = ((lens + 8) // 8 * 8).astype(np.int64)
+        offs = np.concatenate([[0], np.cumsum(2 * H * caps * dh)])[:-1].astype(np.int64)
+        pool = torch.empty(int((2 * H * caps * dh).sum()), dtype=torch.bfloat16, device=DEV).normal_()
+        q = torch.randn((B, H * dh), device=DEV).to(torch.bfloat16)
+        out = torch.empty_like(q)
+        t = lambda a, dt: torch.tensor(a, dtype=dt, device=DEV)
+        args = (1, B, q, H * dh, pool, t(offs, torch.int64), t(caps, torch.int32), t(lens, torch.int32), t(lens - 1, torch.int32),
+                H, dh, 1.0 / np.sqrt(dh), None, 0, out)
+        return lambda s: exe.exe_op_decode_attention(*args, stream=s)
+
+    def projections(M):
+        As = [torch.randn((M, K), device=DEV).to(torch.bfloat16) for _, K in shapes]
+        outs = [torch.empty((M, N), device=DEV, dtype=torch.bfloat16) for N, _ in shapes]
+        wss = [torch.zeros(exe.exe_op_gemm_workspace(1, M, N, K) // 4 + 16, device=DEV, dtype=torch.float32) for N, K in shapes]
+        turn = [0]
+
+        def run(s):
+            turn[0] += 1
+            W = wsets[turn[0] % 3]
+            for i, (N, K) in enumerate(shapes):
+                exe.exe_op_gemm(1, M, N, K, As[i], W[i], None, -1, 1.0, 0, outs[i], wss[i], stream=s)
+        return run
+
+    def timed(fn):
+        fn(2)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn(layers)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / layers * 1e3
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    print("| batch | attention us | projections us | one stream us | two halves, one stream us | two halves, two streams us |\n|---:|" + "---:|" * 5)
+    for B in (256, 128, 64):
+        h = B // 2
+        att, gem = attention(lens_all[:B]), projections(B)
+        att_a, att_b, gem_a, gem_b = attention(lens_all[:h]), attention(lens_all[h:B]), projections(h), projections(h)
+        cur = torch.cuda.current_stream()
+
+        def whole(L):
+            for _ in range(L):
+                att(None)
+                gem(None)
+
+        def halves(L):
+            for _ in range(L):
+                att_a(None)
+                gem_a(None)
+                att_b(None)
+                gem_b(None)
+
+        def streams(L):
+            s1.wait_stream(cur)
+            s2.wait_stream(cur)
+            gem_b(s2)                                  # the second half starts a phase ahead
+            for _ in range(L):
+                att_a(s1)
+                gem_a(s1)
+                att_b(s2)
+                gem_b(s2)
+            cur.wait_stream(s1)
+            cur.wait_stream(s2)
+        only_att = lambda L: [att(None) for _ in range(L)]
+        only_gem = lambda L: [gem(None) for _ in range(L)]
+        print(f"| {B} | {timed(only_att):.1f} | {timed(only_gem):.1f} | {timed(whole):.1f} | {timed(halves):.1f} | {timed(streams):.1f} |", flush=True)
+        del att, gem, att_a, att_b, gem_a, gem_b
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["ingest", "decode_gemm"])
-    ap.add_argument("--rows", default="16,64,153,256")
-    ap.add_argument("--lib", default=None, help="a measurement variant of the library (python -m paper_2404_07947_amd.build --ablate N)")
+    ap.add_argument("what", choices=["ingest", "decode_gemm", "encode_gemm", "two_streams"])
+    ap.add_argument("--rows", default=None)
+    ap.add_argument("--lib", default=None, help="a measurement variant of the library (python -m paper_2404_07947_amd.build --variant ...)")
     args = ap.parse_args()
     if args.lib:
         path = os.path.abspath(args.lib)
         binding.lib_path = lambda: path
     print(f"# {exe.exe_version()}  {binding.lib_path()}", flush=True)
+    rows = lambda dflt: [int(x) for x in (args.rows or dflt).split(",")]
     if args.what == "ingest":
         ingest()
+    elif args.what == "decode_gemm":
+        decode_gemm(rows("16,64,153,256"))
+    elif args.what == "encode_gemm":
+        encode_gemm(rows("16020,16384"))
     else:
-        decode_gemm([int(x) for x in args.rows.split(",")])
+        two_streams()
 
 
 if __name__ == "__main__":

@@ -55,26 +55,26 @@ def build(force: bool = False, verbose: bool = True) -> str:
     return LIB
 
 
-def build_ablation(mask: int, verbose: bool = True) -> str:
-    """Builds libexe_ablate<mask>.so: the library with the tile GEMM compiled as the measurement variant
-    EXE_GEMM_ABLATE=mask (see csrc/kernels_gemm.hip; its results are meaningless, its timing isolates a part of
-    the kernel).  The other objects are the library's own."""
+def build_variant(tag: str, defines, verbose: bool = True) -> str:
+    """Builds libexe_<tag>.so: the library with the tile GEMM compiled as a measurement variant (defines such as
+    -DEXE_GEMM_ABLATE=1 or -DEXE_GEMM_ISSUE_AT=1, see csrc/kernels_gemm.hip; an ablated variant's results are
+    meaningless, its timing isolates a part of the kernel).  The other objects are the library's own."""
     build(verbose=verbose)
-    obj = os.path.join(OBJ, f"kernels_gemm_ablate{mask}.o")
-    cmd = [HIPCC, *FLAGS, f"-DEXE_GEMM_ABLATE={mask}", "-c", os.path.join(CSRC, "kernels_gemm.hip"), "-o", obj]
+    obj = os.path.join(OBJ, f"kernels_gemm_{tag}.o")
+    cmd = [HIPCC, *FLAGS, *defines, "-c", os.path.join(CSRC, "kernels_gemm.hip"), "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l))
     objs = [obj if src == "kernels_gemm.hip" else os.path.join(OBJ, os.path.splitext(src)[0] + ".o") for src in SOURCES]
-    lib = os.path.join(HERE, f"libexe_ablate{mask}.so")
+    lib = os.path.join(HERE, f"libexe_{tag}.so")
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
     return lib
 
 
 if __name__ == "__main__":
-    if "--ablate" in sys.argv:
-        print(build_ablation(int(sys.argv[sys.argv.index("--ablate") + 1])))
+    if "--variant" in sys.argv:
+        print(build_variant(sys.argv[sys.argv.index("--variant") + 1], [a for a in sys.argv if a.startswith("-D")]))
     else:
         build(force="--force" in sys.argv)

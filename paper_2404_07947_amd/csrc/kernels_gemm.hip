@@ -14,7 +14,7 @@
 // whose results are meaningless and whose timing isolates a part: bit 0 drops the MFMAs (the fragment reads from
 // LDS go with them), bit 1 drops the loads of the activation tiles, bit 2 the loads of the weight tiles.  What
 // remains keeps its waits, barriers, epilogue and split-K reduction.  `python -m paper_2404_07947_amd.build
-// --ablate N` builds libexe_ablate<N>.so beside the library.
+// --variant ablate1 -DEXE_GEMM_ABLATE=1` builds libexe_ablate1.so beside the library.
 #include <stdlib.h>
 
 #include <mutex>
@@ -26,6 +26,12 @@
 
 #ifndef EXE_GEMM_ABLATE
 #define EXE_GEMM_ABLATE 0
+#endif
+// Sub-step of a k-tile (8 MFMAs each) at which the second of the four parts of the next stage's loads is issued;
+// the third and fourth follow one sub-step apart.  0 in the library; other values build measurement variants
+// (-1 issues the second part with the first, behind the barrier).
+#ifndef EXE_GEMM_ISSUE_AT
+#define EXE_GEMM_ISSUE_AT 0
 #endif
 
 namespace exe {
@@ -356,6 +362,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
     // A k-tile's loads are issued in four parts spread over 24 MFMAs: a burst of all of them fills the queue of
     // the CU's address unit, and a wave waiting to issue a load issues no MFMA either.
     // (`spread` = 0 issues them all at once behind the barrier.)
+    constexpr int IA = EXE_GEMM_ISSUE_AT > NS - 4 ? NS - 4 : EXE_GEMM_ISSUE_AT;     // all four parts go out inside the k-tile
     constexpr int Q1 = LPX / 4, Q2 = LPX / 2, Q3 = LPX * 3 / 4;
     using X0 = std::integral_constant<int, 0>;
     using X1 = std::integral_constant<int, Q1>;
@@ -424,9 +431,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
 #pragma unroll
                 for (int s = 0; s < NS - 1; ++s) {
                     fetch(st, s + 1);
-                    if (s == 0 && pend) issue_range(fill_st, X1{}, X2{});
-                    if (s == 1 && pend) issue_range(fill_st, X2{}, X3{});
-                    if (s == 2 && pend) {
+                    if (s == IA && pend) issue_range(fill_st, X1{}, X2{});
+                    if (s == IA + 1 && pend) issue_range(fill_st, X2{}, X3{});
+                    if (s == IA + 2 && pend) {
                         issue_range(fill_st, X3{}, X4{});
                         advance();
                     }
@@ -450,6 +457,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
             wait_cnt<LPT*(ST - 2), 0>();
             __syncthreads();
             issue_range(st, X0{}, X1{});
+            if (IA < 0 && NS >= 4 && spread) issue_range(st, X1{}, X2{});
             if (spread) {
                 fill_st = st;
                 pend = true;
