@@ -369,7 +369,9 @@ hipError_t launch_attn_paged(const AttnPagedArgs& a, hipStream_t s)
 
 // ---------------------------------------------------------------- MFMA prefill (bf16, head size 128)
 // A workgroup of 4 waves owns PREFILL_TILE_Q = 128 query rows of one (sequence, head), 32 per wave as two 16-row
-// blocks; three workgroups fit a CU (48 KB of LDS each).  Keys and values pass through LDS in tiles of 64 rows (two
+// blocks; three workgroups fit a CU (48 KB of LDS each, at most 168 registers; the variants with a bias table need
+// more registers than that without spilling, and a spill in the tile loop waits for the tile loads in flight, so
+// they run two per CU).  Keys and values pass through LDS in tiles of 64 rows (two
 // key tiles, double buffered, and one value tile), both by direct global->LDS loads in the same row-major swizzled
 // layout.  Per tile a wave computes
 //   S^T[key][query] = K . Q^T      (MFMA 16x16x32: A = key rows from LDS, B = the wave's query fragments)
@@ -418,7 +420,7 @@ __device__ __forceinline__ float rows_sum(float x)
 }
 
 template <bool CAUSAL, bool BIAS>
-__global__ __launch_bounds__(PF_THREADS, 3) void prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(PF_THREADS, BIAS ? 2 : 3) void prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
                                                                   const int32_t* __restrict__ cu,
                                                                   const int32_t* __restrict__ tiles, int H,
                                                                   float scale, const float* __restrict__ bias_by_dist,
@@ -498,13 +500,18 @@ __global__ __launch_bounds__(PF_THREADS, 3) void prefill_mfma_kernel(const bf16_
     // ---- the three phases of a tile
     auto phase_s = [&](int kt) {
         const unsigned char* sK = pf_smem + (kt & 1) * PF_TILE;
+        // The four swizzled chunk offsets of a lane ((4 ds + g) ^ qi for ds = 0..3) are recomputed per tile from one
+        // register: held across the tile loop they cost four, and a register spilled in this loop puts a full wait
+        // for the tile loads in flight in front of its reload (scratch reloads count with them).
+        int qx = qi;
+        asm volatile("" : "+v"(qx));
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
             s_acc[0][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
             s_acc[1][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ds = 0; ds < 4; ++ds) {
-                bf16x8 fk = *(const bf16x8*)(sK + pf_off(kb * 16 + qi, ds * 4 + g));
+                bf16x8 fk = *(const bf16x8*)(sK + (kb * 16 + qi) * 256 + (((ds * 4 + g) ^ qx) << 4));
                 s_acc[0][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk, qf[0][ds], s_acc[0][kb], 0, 0, 0);
                 s_acc[1][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fk, qf[1][ds], s_acc[1][kb], 0, 0, 0);
             }
@@ -513,7 +520,21 @@ __global__ __launch_bounds__(PF_THREADS, 3) void prefill_mfma_kernel(const bf16_
     // element r of lane (qi, g) in s_acc[qb][kb]: key = kt*64 + kb*16 + 4*g + r, query wq0 + qb*16 + qi.
     // Only tiles that straddle the sequence end or (causal) this wave's diagonal need the per-element mask.
     auto phase_softmax = [&](int kt) {
-        bool masked = BIAS || kt * PF_KT + PF_KT > n || (CAUSAL && kt * PF_KT + PF_KT - 1 > wq0);
+        // With a bias, a tile whose keys all lie at least `radius` before (or after) every query of this wave adds one
+        // constant, the table's first (last) entry, to all of its scores: it takes the path without look-ups with that
+        // constant folded into the exponent.  (The bias table is indexed by the clamped distance.)
+        bool edge = kt * PF_KT + PF_KT > n || (CAUSAL && kt * PF_KT + PF_KT - 1 > wq0);
+        bool masked = BIAS || edge;
+        float cbias = 0.f;
+        if (BIAS && !edge) {
+            if (kt * PF_KT + PF_KT - 1 - wq0 <= -radius) {
+                masked = false;
+                cbias = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sbias[0])));
+            } else if (kt * PF_KT - (wq0 + 31) >= radius) {
+                masked = false;
+                cbias = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sbias[2 * radius])));
+            }
+        }
         float alpha[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -533,8 +554,10 @@ __global__ __launch_bounds__(PF_THREADS, 3) void prefill_mfma_kernel(const bf16_
                             rel = rel < -radius ? -radius : (rel > radius ? radius : rel);
                             v += sbias[rel + radius];
                         }
-                        bool ok = key < n && (!CAUSAL || key <= qpos);
-                        v = ok ? v : -INFINITY;
+                        if (edge) {
+                            bool ok = key < n && (!CAUSAL || key <= qpos);
+                            v = ok ? v : -INFINITY;
+                        }
                         s_acc[qb][kb][r] = v;
                         mx = fmaxf(mx, v);
                     }
@@ -544,19 +567,20 @@ __global__ __launch_bounds__(PF_THREADS, 3) void prefill_mfma_kernel(const bf16_
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s_acc[qb][kb][r]);
-                mx *= sc;
+                mx = fmaf(mx, sc, cbias);
             }
             mx = rows_max(mx);
             float m_new = fmaxf(m_run[qb], mx);
             float mref = m_new == -INFINITY ? 0.f : m_new;
             alpha[qb] = fast_exp2(m_run[qb] - mref);
             float mul = masked ? 1.f : sc;
+            float shift = cbias - mref;             // cbias is 0 on the path with look-ups
             float rs = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float p = fast_exp2(fmaf(s_acc[qb][kb][r], mul, -mref));
+                    float p = fast_exp2(fmaf(s_acc[qb][kb][r], mul, shift));
                     s_acc[qb][kb][r] = p;
                     rs += p;
                 }
