@@ -88,13 +88,20 @@ struct AttnPackedArgs {      // ragged prefill over packed qkv [T, 3*H*dh]
     float scale;
     const float* bias_by_dist; int bias_radius;
     void* out;               // [T, H*dh]
-    // tile list for the MFMA kernel: (seq, first query row) pairs, longest work first
+    // tile list for the MFMA kernel: (seq, first query row) pairs in the order prefill_tile_order gives
     const int32_t* tiles; int n_tiles;
     int force_generic;
     int max_len = 0;         // longest sequence of the batch (0 = unknown: T is taken)
 };
 bool prefill_mfma_supported(int dtype, int dh);
 constexpr int PREFILL_TILE_Q = 128;
+// Appends the (seq, first query row) pairs of a batch's 128-row query tiles to `tiles`: sequences longest first, the
+// tiles of one sequence together, last rows (causal: most keys) first.  The tiles of a sequence read the same keys
+// and values, and the kernel's workgroup numbering puts neighbours of this list (for one head) on one XCD at about
+// the same time, so that they arrive in that XCD's L2 once; longest first keeps the short work for the end of the
+// launch.  (Measured against most-work-first over the whole batch and over groups of 8 to 40 tiles: this order is
+// the fastest or within 1 % of it on ragged and uniform batches, and halves the kernel's HBM reads.)
+void prefill_tile_order(const int32_t* lens, int n_seqs, std::vector<int32_t>& tiles);
 hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s);
 
 }  // namespace exe

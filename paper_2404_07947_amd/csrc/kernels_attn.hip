@@ -429,8 +429,20 @@ __global__ __launch_bounds__(PF_THREADS, BIAS ? 2 : 3) void prefill_mfma_kernel(
     extern __shared__ __align__(16) unsigned char pf_smem[];      // 2 key tiles, then 1 value tile
     __shared__ float sbias[BIAS ? 1024 : 1];
 
-    int sb = tiles[blockIdx.x * 2], q0 = tiles[blockIdx.x * 2 + 1];
-    int h = blockIdx.y;
+    // Workgroup -> (tile, head).  Workgroups go to the 8 XCDs round-robin in launch order.  With a multiple of 8 heads,
+    // XCD x takes heads x, x + 8, ...: its j-th workgroup is tile j / (H/8) for its head number j % (H/8), so the
+    // tiles of one sequence and head (neighbours in the list, readers of the same keys and values) share an L2 and
+    // run side by side.  Otherwise heads vary fastest.
+    int tile, h;
+    if ((H & 7) == 0) {
+        int hpx = H >> 3, j = blockIdx.x >> 3;
+        tile = j / hpx;
+        h = (blockIdx.x & 7) + 8 * (j - tile * hpx);
+    } else {
+        tile = blockIdx.x / H;
+        h = blockIdx.x - tile * H;
+    }
+    int sb = tiles[tile * 2], q0 = tiles[tile * 2 + 1];
     int t0 = cu[sb], n = cu[sb + 1] - t0;
     int inner = H * PF_DH;
     int64_t ld = 3 * (int64_t)inner;
@@ -668,6 +680,18 @@ __global__ __launch_bounds__(PF_THREADS, BIAS ? 2 : 3) void prefill_mfma_kernel(
 
 bool prefill_mfma_supported(int dtype, int dh) { return dtype == DT_BF16 && dh == PF_DH; }
 
+void prefill_tile_order(const int32_t* lens, int n_seqs, std::vector<int32_t>& tiles)
+{
+    std::vector<int> order(n_seqs);
+    for (int i = 0; i < n_seqs; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return lens[x] > lens[y]; });
+    for (int i : order)
+        for (int q0 = (lens[i] - 1) / PREFILL_TILE_Q * PREFILL_TILE_Q; q0 >= 0; q0 -= PREFILL_TILE_Q) {
+            tiles.push_back(i);
+            tiles.push_back(q0);
+        }
+}
+
 hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
@@ -685,7 +709,8 @@ hipError_t launch_attn_packed(const AttnPackedArgs& a, hipStream_t s)
         });
     }
     if (mfma_shape && mfma_fits) {
-        dim3 grid(a.n_tiles, a.H);
+        if ((int64_t)a.n_tiles * a.H > 0x7fffffff) return hipErrorInvalidValue;
+        dim3 grid((unsigned)(a.n_tiles * a.H));
         const bf16_t* qkv = (const bf16_t*)a.qkv;
         bf16_t* out = (bf16_t*)a.out;
         constexpr int lds = PF_LDS;

@@ -661,7 +661,6 @@ static void fill_encode_desc(exe_model* m, Stager& st, EncodeDesc& d, int n, con
     int32_t* h_xcap = st.take<int32_t>(n, &d.xcap);
     int64_t* h_base = st.take<int64_t>(n, &d.base);
     int64_t* h_xbase = st.take<int64_t>(n, &d.xbase);
-    std::vector<std::pair<int, std::pair<int, int>>> tl;   // (work, (seq, q0))
     int t = 0;
     for (int i = 0; i < n; ++i) {
         h_cu[i] = t;
@@ -675,14 +674,13 @@ static void fill_encode_desc(exe_model* m, Stager& st, EncodeDesc& d, int n, con
         h_xcap[i] = encdec ? round8(lens[i]) : 0;
         h_xbase[i] = encdec ? fresh[i].xbase : 0;
         h_last[i] = t - 1;
-        for (int q0 = 0; q0 < lens[i]; q0 += PREFILL_TILE_Q)
-            tl.push_back({encdec ? lens[i] : std::min(lens[i], q0 + PREFILL_TILE_Q), {i, q0}});
     }
     h_cu[n] = t;
-    std::stable_sort(tl.begin(), tl.end(), [](const auto& x, const auto& y) { return x.first > y.first; });
-    int32_t* h_tiles = st.take<int32_t>(2 * tl.size(), &d.tiles);
-    d.n_tiles = (int)tl.size();
-    for (size_t k = 0; k < tl.size(); ++k) { h_tiles[2 * k] = tl[k].second.first; h_tiles[2 * k + 1] = tl[k].second.second; }
+    std::vector<int32_t> tl;
+    prefill_tile_order(lens.data(), n, tl);
+    int32_t* h_tiles = st.take<int32_t>(tl.size(), &d.tiles);
+    d.n_tiles = (int)(tl.size() / 2);
+    std::copy(tl.begin(), tl.end(), h_tiles);
 }
 
 extern "C" int exe_encode(exe_model_t* m, int32_t n, const int32_t* seq_ids, const int32_t* input_lengths,
@@ -1747,8 +1745,7 @@ extern "C" int exe_op_prefill_attention(void* hip_stream, int32_t dtype, int32_t
     if (dh != 64 && dh != 128) return fail(EXE_ERR_SHAPE, "head_dim must be 64 or 128");
     hipStream_t s = (hipStream_t)hip_stream;
     int T = cu_seqlens[n_seqs];
-    std::vector<int32_t> host;
-    std::vector<std::pair<int, std::pair<int, int>>> tl;
+    std::vector<int32_t> host, lens(n_seqs);
     host.resize((size_t)2 * T + n_seqs + 1);
     int max_len = 0;
     for (int i = 0; i < n_seqs; ++i) {
@@ -1756,17 +1753,18 @@ extern "C" int exe_op_prefill_attention(void* hip_stream, int32_t dtype, int32_t
         if (L < 1) return fail(EXE_ERR_BAD_LENGTH, "empty sequence");
         max_len = std::max(max_len, L);
         for (int p = 0; p < L; ++p) { host[cu_seqlens[i] + p] = i; host[T + cu_seqlens[i] + p] = p; }
-        for (int q0 = 0; q0 < L; q0 += PREFILL_TILE_Q) tl.push_back({causal ? std::min(L, q0 + PREFILL_TILE_Q) : L, {i, q0}});
+        lens[i] = L;
     }
     for (int i = 0; i <= n_seqs; ++i) host[2 * T + i] = cu_seqlens[i];
-    std::stable_sort(tl.begin(), tl.end(), [](const auto& x, const auto& y) { return x.first > y.first; });
-    for (auto& t : tl) { host.push_back(t.second.first); host.push_back(t.second.second); }
+    size_t tiles_at = host.size();
+    prefill_tile_order(lens.data(), n_seqs, host);
+    int n_tiles = (int)((host.size() - tiles_at) / 2);
     int32_t* dev = nullptr;
     HIP_TRY(hipMalloc((void**)&dev, host.size() * 4));
     hipError_t e = hipMemcpyAsync(dev, host.data(), host.size() * 4, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) {
         AttnPackedArgs a{dtype, T, H, dh, n_seqs, qkv, dev, dev + T, dev + 2 * T, causal, scale, bias_by_dist, bias_radius,
-                         out, dev + 2 * T + n_seqs + 1, (int)tl.size(), force_generic};
+                         out, dev + 2 * T + n_seqs + 1, n_tiles, force_generic};
         a.max_len = max_len;
         e = launch_attn_packed(a, s);
     }
