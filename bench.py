@@ -93,7 +93,7 @@ def accumulate(acc, rows):
 # per kernel at the OPT-13B bench shapes by a separate counter run (profiles/traffic_opt13b_kernels.md gives the
 # command and the table; regenerate it whenever a kernel it covers changes).  gemm_skinny: at the job's mean decode
 # batch of 153 rows (1.20 at 64 rows, 1.51 at 256: the split-K partial sums).  A class not listed reports null.
-TRAFFIC_RATIO = {"gemm_tile": 6.04, "gemm_skinny": 1.38, "decode_attn": 1.0, "cross_attn": 1.0, "prefill_attn": 1.64}
+TRAFFIC_RATIO = {"gemm_tile": 6.04, "gemm_skinny": 1.38, "decode_attn": 1.0, "cross_attn": 1.0, "prefill_attn": 1.02}
 
 
 def roofline_entry(kind, a):
