@@ -8,7 +8,7 @@
   python3 microbench.py decode_gemm [--rows 16,64,153,256] [--lib PATH]
       the four projections of an OPT-13B layer (QKV, out, FFN1, FFN2) at decode row counts, split-K reductions included,
       with the weights rotating through HBM-resident copies; --lib takes a measurement variant of the library built by
-      `python -m paper_2404_07947_amd.build --variant ablateN -DEXE_GEMM_ABLATE=N` (N: 1 no MFMA, 2 no activation loads, 4 no weight loads, sums
+      `python -m paper_2404_07947_amd.build --variant ablateN -DEXE_GEMM_ABLATE=N` (N: 1 no MFMA, 2 no activation loads, 4 no weight loads, 32 no epilogue, sums
       combine), whose results are meaningless and whose timing isolates a part of the kernel.
   python3 microbench.py encode_gemm [--rows 16020,16384] [--lib PATH]
       the same four projections at encode row counts; --lib e.g. a variant with the loads of a k-tile issued later

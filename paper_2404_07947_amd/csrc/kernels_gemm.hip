@@ -12,7 +12,8 @@
 //
 // EXE_GEMM_ABLATE (a compile-time bit mask, 0 in the library proper) builds measurement variants of the tile kernel
 // whose results are meaningless and whose timing isolates a part: bit 0 drops the MFMAs (the fragment reads from
-// LDS go with them), bit 1 drops the loads of the activation tiles, bit 2 the loads of the weight tiles.  What
+// LDS go with them), bit 1 drops the loads of the activation tiles, bit 2 the loads of the weight tiles, bit 5 the
+// epilogue (no output is written; a split-K reduction still runs, on whatever the workspace holds).  What
 // remains keeps its waits, barriers, epilogue and split-K reduction.  `python -m paper_2404_07947_amd.build
 // --variant ablate1 -DEXE_GEMM_ABLATE=1` builds libexe_ablate1.so beside the library.
 #include <stdlib.h>
@@ -473,7 +474,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_tile_kernel(
         {
             unsigned stg = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds + ST * STAGE + wave * (EN * 128);
             int row0 = m0 + wm * WM, col0 = n0 + wn * WN;
-            if (n_split > 1)
+            if (EXE_GEMM_ABLATE & 32) {            // measurement variant: no epilogue, the accumulators are only kept alive
+#pragma unroll
+                for (int i = 0; i < TN; ++i)
+#pragma unroll
+                    for (int j = 0; j < TM; ++j) asm volatile("" ::"v"(acc[i][j]));
+            } else if (n_split > 1)
                 epilogue_tiles<TM, TN, EN, EPI_PARTIAL>(acc, stg, lane, row0, col0, M, N, nullptr, 1.f, partial + (int64_t)z * M * N, nullptr);
             else if (out_mode == OUT_RESID)
                 epilogue_tiles<TM, TN, EN, EPI_RESID>(acc, stg, lane, row0, col0, M, N, bias, alpha, (float*)out, nullptr);
