@@ -310,6 +310,12 @@ int exe_op_norm(void* hip_stream, int32_t dtype, int32_t rms, const float* x, co
 int exe_op_prefill_attention(void* hip_stream, int32_t dtype, int32_t n_seqs, const int32_t* cu_seqlens,
                              const void* qkv, int32_t H, int32_t dh, float scale, int32_t causal,
                              const float* bias_by_dist, int32_t bias_radius, void* out, int32_t force_generic);
+/* The launch order of the MFMA prefill kernel's query tiles (host function; lets a test check the list without a
+ * GPU): for sequences of the given lengths (host, each >= 1), pairs (sequence, first query row) of the 128-row tiles,
+ * written to tiles[2 * k], tiles[2 * k + 1].  Sequences go longest first (ties in their given order), a sequence's
+ * tiles together, last rows first.  *n_tiles receives the count; cap = capacity of tiles in pairs; a list that does
+ * not fit is EXE_ERR_ARG with *n_tiles set to the count needed. */
+int exe_op_prefill_tiles(int32_t n_seqs, const int32_t* lengths, int32_t* tiles, int32_t cap, int32_t* n_tiles);
 /* Decode attention: q [B, H*dh] dtype; per sequence b the keys are at kv + k_offset[b] (elements) laid out
  * [H][cap[b]][dh] and the values at kv + k_offset[b] + H*cap[b]*dh; len[b] keys are valid; the query's
  * position is qpos[b] (for the bias only: index clamp(j - qpos)+radius).  All arrays device.  out [B, H*dh]. */

@@ -13,7 +13,7 @@ _lib = None
 DECLARED_SYMBOLS = [
     "exe_expected_weights", "exe_model_load", "exe_model_free", "exe_encode", "exe_decode_step",
     "exe_seq_release", "exe_seq_length", "exe_kv_stats", "exe_seq_export_bytes", "exe_seq_export", "exe_seq_import", "exe_seq_reserve", "exe_kv_compact", "exe_profile", "exe_run_rra", "exe_kernel_timing",
-    "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_gemm_plan", "exe_op_gemm_ld", "exe_op_gemm_noalloc", "exe_op_gemm_noalloc_max_workspace", "exe_op_paged_index_check", "exe_op_norm", "exe_op_prefill_attention",
+    "exe_kernel_times", "exe_op_gemm", "exe_op_gemm_workspace", "exe_op_gemm_plan", "exe_op_gemm_ld", "exe_op_gemm_noalloc", "exe_op_gemm_noalloc_max_workspace", "exe_op_paged_index_check", "exe_op_norm", "exe_op_prefill_attention", "exe_op_prefill_tiles",
     "exe_op_decode_attention", "exe_op_decode_attention_paged", "exe_probe_peaks", "exe_probe_ingest", "exe_op_argmax", "exe_rel_bucket", "exe_last_error", "exe_version",
     # exe_sched.h (host only)
     "exe_sim_completion", "exe_sim_step_ms", "exe_sim_rra", "exe_sim_waa", "exe_sched_search", "exe_sched_rra",
@@ -143,6 +143,7 @@ def lib():
     L.exe_op_gemm_noalloc_max_workspace.restype = C.c_uint64
     L.exe_op_norm.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, C.c_float, C.c_float, vp]
     L.exe_op_prefill_attention.argtypes = [vp, i32, i32, ip, vp, i32, i32, C.c_float, i32, vp, i32, vp, i32]
+    L.exe_op_prefill_tiles.argtypes = [i32, ip, ip, i32, ip]
     L.exe_op_decode_attention.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, vp, i32, vp]
     L.exe_op_decode_attention_paged.argtypes = [vp, i32, i32, vp, i32, vp, vp, i32, i32, vp, vp, i32, i32, C.c_float, vp, i32,
                                                 i32, vp]
@@ -367,6 +368,16 @@ def exe_op_paged_index_check(dtype: int, dh: int, block_size: int, n_waves: int,
 def exe_op_norm(dtype, rms, x, row_index, rows, d, gain, shift, eps, out_scale, out, stream=None):
     _check(lib().exe_op_norm(_stream_ptr(stream), dtype, rms, _dev(x), _dev(row_index), rows, d, _dev(gain),
                              _dev(shift), eps, out_scale, _dev(out)))
+
+
+def exe_op_prefill_tiles(lengths):
+    """The (sequence, first query row) pairs of the prefill kernel's query tiles, in launch order (host only)."""
+    lens = np.ascontiguousarray(lengths, dtype=np.int32)
+    cap = int((lens.astype(np.int64) + 127).sum() // 128 + len(lens))
+    out = np.zeros((max(cap, 1), 2), dtype=np.int32)
+    n = C.c_int32()
+    _check(lib().exe_op_prefill_tiles(len(lens), _ip(lens), _ip(out), cap, C.byref(n)))
+    return out[:n.value].copy()
 
 
 def exe_op_prefill_attention(dtype, cu_seqlens, qkv, H, dh, scale, causal, bias_by_dist, bias_radius, out,

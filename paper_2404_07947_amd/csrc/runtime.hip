@@ -1775,6 +1775,19 @@ extern "C" int exe_op_prefill_attention(void* hip_stream, int32_t dtype, int32_t
     return EXE_OK;
 }
 
+extern "C" int exe_op_prefill_tiles(int32_t n_seqs, const int32_t* lengths, int32_t* tiles, int32_t cap, int32_t* n_tiles)
+{
+    if (n_seqs < 0 || (n_seqs > 0 && !lengths) || !n_tiles || cap < 0 || (cap > 0 && !tiles)) return fail(EXE_ERR_ARG, "bad tile list arguments");
+    for (int i = 0; i < n_seqs; ++i)
+        if (lengths[i] < 1) return fail(EXE_ERR_BAD_LENGTH, "empty sequence");
+    std::vector<int32_t> tl;
+    prefill_tile_order(lengths, n_seqs, tl);
+    *n_tiles = (int32_t)(tl.size() / 2);
+    if (*n_tiles > cap) return fail(EXE_ERR_ARG, "tile list needs %d pairs, capacity %d", *n_tiles, cap);
+    std::copy(tl.begin(), tl.end(), tiles);
+    return EXE_OK;
+}
+
 extern "C" int exe_op_decode_attention(void* hip_stream, int32_t dtype, int32_t B, const void* q, int32_t q_stride,
                                        const void* kv, const int64_t* k_offset, const int32_t* cap, const int32_t* len,
                                        const int32_t* qpos, int32_t H, int32_t dh, float scale,

@@ -72,3 +72,31 @@ def test_config_errors_are_reported_not_raised_as_crashes():
     assert L.exe_model_free(None) == -1
     assert L.exe_seq_release(None, 0, None) == -1
     assert b"null" in L.exe_last_error()
+
+
+def test_prefill_tile_list_covers_every_query_tile_once_in_launch_order():
+    """Host logic of the MFMA prefill launch: every 128-row query tile of every sequence appears exactly once; sequences
+    go longest first (ties in the given order), a sequence's tiles together, last rows first."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    batches = [[1], [128], [129], [1024, 1024, 1024], [64, 1024, 300, 300, 1, 127, 128, 129, 2048]]
+    batches += [list(rng.integers(1, 1100, size=int(rng.integers(1, 40)))) for _ in range(20)]
+    for lens in batches:
+        t = exe.exe_op_prefill_tiles(lens)
+        want = {(i, q0) for i, n in enumerate(lens) for q0 in range(0, int(n), 128)}
+        got = [tuple(int(v) for v in p) for p in t]
+        assert len(got) == len(want) and set(got) == want, lens
+        seqs = [i for i, _ in got]
+        order = [s for k, s in enumerate(seqs) if k == 0 or seqs[k - 1] != s]
+        assert len(order) == len(lens), ("a sequence's tiles are not together", lens)
+        assert order == sorted(range(len(lens)), key=lambda i: -int(lens[i])), lens      # stable: ties keep their order
+        for i in range(len(lens)):
+            q = [q0 for s, q0 in got if s == i]
+            assert q == sorted(q, reverse=True)
+    with pytest.raises(exe.ExeError) as e:
+        exe.exe_op_prefill_tiles([5, 0, 7])
+    assert e.value.code == -5
+    import ctypes
+    n = ctypes.c_int32()
+    lens = (ctypes.c_int32 * 2)(300, 5)
+    assert exe.lib().exe_op_prefill_tiles(2, lens, None, 0, ctypes.byref(n)) == -1 and n.value == 4
