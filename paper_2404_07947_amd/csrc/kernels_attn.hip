@@ -14,6 +14,7 @@
 //    one's accumulators.
 #include <stdio.h>
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
