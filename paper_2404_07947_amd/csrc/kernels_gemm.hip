@@ -702,12 +702,23 @@ static int split_rows(int dtype, int M, int N, int K)
     int tn = (N + 255) / 256, tm = (M + 255) / 256, total = tm * tn;
     int rounds = total / G;
     if (rounds < 1 || total == rounds * G) return M;
-    int tm1 = rounds * G / tn;
-    if (tm1 < 1 || tm1 >= tm) return M;
-    int M1 = tm1 * 256;
     double whole = plan_cost(C256x256, 1, M, N, K);
-    double parts = plan_cost(C256x256, 1, M1, N, K) + make_plan(dtype, M - M1, N, K).cost;
-    return parts < whole ? M1 : M;
+    // Candidates for the first launch: the most row tiles that fill whole rounds, and the largest multiple of 64 row
+    // tiles.  With a multiple of 64 every XCD keeps one group of 8 row tiles for the whole launch and all eight walk
+    // the weight columns in step; measured, a round of such a launch takes 3-6 % less (16 384 rows against 17 120 -
+    // 17 352 at the OPT-13B shape: 1826 us + 127 us for the rest against 2049 us in one launch of 16 rounds).
+    int best = M;
+    double best_cost = whole;
+    int cand[2] = {rounds * G / tn, tm / 64 * 64};
+    for (int tm1 : cand) {
+        if (tm1 < 1 || tm1 >= tm) continue;
+        int M1 = tm1 * 256;
+        double first = plan_cost(C256x256, 1, M1, N, K);
+        if (tm1 % 64 == 0) first *= 0.95;
+        double parts = first + make_plan(dtype, M - M1, N, K).cost;
+        if (parts < best_cost) { best_cost = parts; best = M1; }
+    }
+    return best;
 }
 
 void gemm_plan_info(int dtype, int M, int N, int K, int* route, int* cfg, int* splits, int* rows_first)
