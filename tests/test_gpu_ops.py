@@ -475,6 +475,51 @@ def test_prefill_attention_long(causal, use_bias):
     assert worst < 2.0 ** -6, worst
 
 
+@pytest.mark.parametrize("H,causal,use_bias", [(40, 1, 0), (128, 0, 1)])
+def test_prefill_attention_bench_batch_is_order_independent(H, causal, use_bias):
+    """At the benchmarks' own sizes (OPT-13B: 32 sequences, 40 heads, causal; T5-11B: 16 sequences, 128 heads, bias) the
+    oracle samples a few rows; what holds at any size is that a sequence's rows do not depend on where it stands in the
+    batch: the launch order (sequences longest first, heads dealt to XCDs) changes with the permutation, the rows of
+    every sequence must stay bit-identical."""
+    dh, R = 128, 128
+    job = wl.workload_opt13b(256) if causal else wl.workload_t5(64)
+    lens = [int(x) for x in job.in_len[:32 if causal else 16]]
+    inner = H * dh
+    scale = 1.0 / np.sqrt(dh) if causal else 0.11
+    tab = bias_table(H, R, 77).to(DEV) if use_bias else None
+    g = torch.Generator(device=DEV).manual_seed(5)
+    rows = {i: torch.randn((L, 3 * inner), device=DEV, generator=g).to(torch.bfloat16) for i, L in enumerate(lens)}
+
+    def run(order):
+        cu = np.concatenate([[0], np.cumsum([lens[i] for i in order])]).astype(np.int32)
+        qkv = torch.cat([rows[i] for i in order])
+        out = torch.zeros((int(cu[-1]), inner), dtype=torch.bfloat16, device=DEV)
+        exe.exe_op_prefill_attention(BF16, cu, qkv, H, dh, scale, causal, tab, R, out)
+        torch.cuda.synchronize()
+        return {i: out[cu[k]:cu[k + 1]].clone() for k, i in enumerate(order)}, qkv, cu
+
+    base, _, _ = run(list(range(len(lens))))
+    perm = list(np.random.default_rng(9).permutation(len(lens)))
+    other, _, _ = run([int(i) for i in perm])
+    for i in range(len(lens)):
+        assert torch.equal(base[i], other[i]), i
+    # sampled rows against the oracle: first, last and a middle row of the longest and the shortest sequence, three heads
+    worst = 0.0
+    for s in (int(np.argmax(lens)), int(np.argmin(lens))):
+        L = lens[s]
+        x = rows[s].float().cpu().numpy()
+        got = base[s].float().cpu().numpy()
+        for h in (0, H // 2 + 1, H - 1):
+            Ks = x[:, inner + h * dh: inner + (h + 1) * dh]
+            Vs = x[:, 2 * inner + h * dh: 2 * inner + (h + 1) * dh]
+            for i in (0, L // 2, L - 1):
+                nk = i + 1 if causal else L
+                bias = tab.cpu().numpy()[h][np.clip(np.arange(nk) - i, -R, R) + R] if use_bias else None
+                ref = oracle_attention(x[i, h * dh:(h + 1) * dh], Ks[:nk], Vs[:nk], float(np.float32(scale)), bias)
+                worst = max(worst, relerr(got[i, h * dh:(h + 1) * dh], ref))
+    assert worst < 2.0 ** -6, worst
+
+
 def random_prefill_batches():
     rng = np.random.default_rng(91)
     cases = []
